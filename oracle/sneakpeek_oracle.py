@@ -1,0 +1,348 @@
+"""Plain CPU oracle for SneakPeek scoring and batch-aware greedy scheduling.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct checker
+that the HIP library is compared against.  It is NumPy in float64, follows the
+paper's definitions step by step, shares no code with the HIP path and is
+never imported by it; only the tests, the smoke check and the benchmark's
+CPU-baseline leg may call it.
+
+What each function follows:
+
+* head_logits / posterior  -- Def. 4.1.1, 4.1.2 (a SneakPeek model turns a
+  request's data into class probabilities theta).  The parametric heads
+  (logistic, one-hidden-layer ReLU MLP, softmax output) are the workload's.
+* expected_accuracy        -- Sec. 4.1, eq. (9): Accuracy(m) = sum_c theta_c *
+  recall_c(m), with theta treated as a per-request parameter.
+* accuracy_from_confusion  -- Sec. 4.1, eq. (7): tr(Z) / sum(Z).
+* request_priority         -- Sec. 5.1.1, eq. (12), population variance.
+* penalty                  -- Sec. 6.1 (step / linear / sigmoid penalties).
+* utility                  -- Sec. 3.1, eq. (2).
+* service_order            -- Alg. 1 ("requests in g sorted by priority").
+* Window.*                 -- Alg. 1 generalised to batch-capped greedy rounds;
+  eq. (1) clock with the batch as the unit; eq. (13) arg max.
+* dirichlet_posterior_mean -- Sec. 4.2, eq. (10)-(11).
+
+Readings of points the paper leaves open (all listed in the design notes):
+the linear and sigmoid penalties are capped with min(1, .) (the printed
+max(1, .) would make every miss worse than the step penalty and break the
+monotone 0..1 range eq. (2) needs); deadlines are relative to the window's
+start and must be positive; a deadline is missed only when completion is
+strictly later; exp(-d) in eq. (12) takes the remaining time in units of a
+timescale T_d (1000 ms by default); the per-request weight w multiplies both
+the key and the reported utility (w = 1 recovers the paper); every member of a
+batch completes at t + L[m,b]; a request is dead once its penalty would be 1
+even alone on the fastest variant, and dead requests never come back.
+
+Parity status: every function here is pinned by tests/test_oracle_*.py
+against closed forms, the paper's worked numbers, or brute force, except the
+paper's dataset-level results (utility gains on MMAct / Speech Commands /
+MIT-BIH), which need data that is not available: parity unpinned for those.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PEN_STEP, PEN_LINEAR, PEN_SIGMOID = 0, 1, 2
+
+
+# --------------------------------------------------------------------------
+# inputs
+# --------------------------------------------------------------------------
+def widen(a):
+    """Exact float64 view of an input array (float32, or uint16 bfloat16 bits)."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# SneakPeek posterior and data-aware accuracy (Sec. 4)
+# --------------------------------------------------------------------------
+def head_logits(x, W1, b1, W2=None, b2=None):
+    """Class scores of the SneakPeek head for rows of x.  Logistic: x W1 + b1.
+    MLP: relu(x W1 + b1) W2 + b2.  The hidden activations are not rounded."""
+    x = widen(x)
+    z = x @ widen(W1) + widen(b1)
+    if W2 is not None:
+        h = np.maximum(z, 0.0)
+        z = h @ widen(W2) + widen(b2)
+    return z
+
+
+def posterior(z):
+    """theta = softmax(z) along the last axis (SneakPeek probabilities, Def. 4.1.2)."""
+    z = np.asarray(z, dtype=np.float64)
+    e = np.exp(z - z.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def expected_accuracy(theta, recall):
+    """eq. (9): EA[i,m] = sum_c theta[i,c] * recall[m,c]."""
+    return np.asarray(theta, dtype=np.float64) @ widen(recall).T
+
+
+def accuracy_from_confusion(Z):
+    """eq. (7): profiled accuracy tr(Z) / sum(Z) of a confusion matrix
+    (rows = true class, columns = predicted class)."""
+    Z = np.asarray(Z, dtype=np.float64)
+    return np.trace(Z) / Z.sum()
+
+
+def class_frequency_from_confusion(Z):
+    """theta of the test set: row sums over the grand total (eq. (8))."""
+    Z = np.asarray(Z, dtype=np.float64)
+    return Z.sum(axis=1) / Z.sum()
+
+
+def recall_from_confusion(Z):
+    """Per-class recall z_ii / sum_j z_ij (eq. (9))."""
+    Z = np.asarray(Z, dtype=np.float64)
+    return np.diag(Z) / Z.sum(axis=1)
+
+
+def dirichlet_posterior_mean(alpha, y):
+    """Mean of Dirichlet(alpha + y), eq. (10)-(11)."""
+    p = np.asarray(alpha, dtype=np.float64) + np.asarray(y, dtype=np.float64)
+    return p / p.sum()
+
+
+# --------------------------------------------------------------------------
+# priority, penalty, utility (Sec. 3.1, 5.1, 6.1)
+# --------------------------------------------------------------------------
+def population_variance(v, axis=-1):
+    v = np.asarray(v, dtype=np.float64)
+    mu = v.mean(axis=axis, keepdims=True)
+    return ((v - mu) ** 2).mean(axis=axis)
+
+
+def request_priority(acc_set, deadline_rel_ms, weight=1.0, timescale_ms=1000.0):
+    """eq. (12): (1 + Var[Accuracy(M_a)]) * exp(-d), times the request weight.
+    `acc_set` holds the request's accuracies over its application's variants
+    along the last axis."""
+    var = population_variance(acc_set, axis=-1)
+    d = widen(deadline_rel_ms) / float(timescale_ms)
+    return widen(weight) * (1.0 + var) * np.exp(-d)
+
+
+def penalty(kind, deadline, completion):
+    """gamma(d, e) of Sec. 6.1; 0 when on time, within [0, 1] when late."""
+    d = np.asarray(deadline, dtype=np.float64)
+    e = np.asarray(completion, dtype=np.float64)
+    d, e = np.broadcast_arrays(d, e)
+    late = e > d
+    if kind == PEN_STEP:
+        return late.astype(np.float64)
+    x = 1.0 - (2.0 * d - e) / d          # = (e - d) / d
+    g = np.zeros(d.shape, dtype=np.float64)
+    if kind == PEN_LINEAR:
+        g[late] = np.minimum(1.0, x[late])
+        return g
+    if kind == PEN_SIGMOID:
+        mid = late & (x < 1.0)
+        xm = x[mid]
+        g[mid] = np.minimum(1.0, 1.0 / (1.0 + (xm / (1.0 - xm)) ** -3.0))
+        g[late & (x >= 1.0)] = 1.0
+        return g
+    raise ValueError(f"unknown penalty kind {kind}")
+
+
+def utility(accuracy, kind, deadline, completion):
+    """eq. (2): Accuracy(m) * [1 - gamma(d, t + l(m))]."""
+    return np.asarray(accuracy, dtype=np.float64) * (1.0 - penalty(kind, deadline, completion))
+
+
+def is_dead(kind, deadline, earliest_completion):
+    """A request whose penalty is already 1 on the earliest possible
+    completion can no longer earn utility: step -> e > d, else e >= 2 d."""
+    d = np.asarray(deadline, dtype=np.float64)
+    e = np.asarray(earliest_completion, dtype=np.float64)
+    if kind == PEN_STEP:
+        return e > d
+    return e >= 2.0 * d
+
+
+# --------------------------------------------------------------------------
+# scoring pass over a queue
+# --------------------------------------------------------------------------
+def score_requests(profile, requests, chunk=16384, return_theta=False):
+    """Posterior -> expected accuracy -> priority key for every request.
+    Returns EA [N, Mmax] (zero beyond an application's variants) and key [N]."""
+    n = int(requests.app.shape[0])
+    A = int(profile.n_apps)
+    m_max = int(np.max(profile.n_models))
+    ea = np.zeros((n, m_max), dtype=np.float64)
+    key = np.zeros(n, dtype=np.float64)
+    thetas = [None] * n if return_theta else None
+    for a in range(A):
+        sel = np.nonzero(requests.app == a)[0]
+        M = int(profile.n_models[a])
+        for s in range(0, sel.shape[0], chunk):
+            ids = sel[s:s + chunk]
+            z = head_logits(requests.x[ids], profile.W1[a], profile.b1[a], profile.W2[a], profile.b2[a])
+            th = posterior(z)
+            e = expected_accuracy(th, profile.acc[a])
+            ea[ids, :M] = e
+            key[ids] = request_priority(e, requests.deadline_rel_ms[ids], requests.weight[ids],
+                                        profile.prio_timescale_ms)
+            if return_theta:
+                for j, i in enumerate(ids):
+                    thetas[i] = th[j]
+    if return_theta:
+        return ea, key, thetas
+    return ea, key
+
+
+def service_order(app, key, n_apps):
+    """Per application, request ids by (key descending, id ascending)."""
+    out = []
+    for a in range(int(n_apps)):
+        sel = np.nonzero(np.asarray(app) == a)[0]
+        out.append(sel[np.argsort(-np.asarray(key, dtype=np.float64)[sel], kind="stable")])
+    return out
+
+
+# --------------------------------------------------------------------------
+# greedy batch-selection rounds
+# --------------------------------------------------------------------------
+class Window:
+    """State of one scheduling window: who is still pending, the worker clock
+    t (ms since the window's start), and what has been assigned so far."""
+
+    def __init__(self, profile, requests, ea=None, key=None):
+        self.p = profile
+        self.n = int(requests.app.shape[0])
+        self.app = np.asarray(requests.app)
+        self.D = widen(requests.deadline_rel_ms)
+        self.w = widen(requests.weight)
+        if ea is None or key is None:
+            ea, key = score_requests(profile, requests)
+        self.ea = np.asarray(ea, dtype=np.float64)
+        self.key = np.asarray(key, dtype=np.float64)
+        self.order = service_order(self.app, self.key, profile.n_apps)
+        self.lat = [widen(l) for l in profile.lat_ms]
+        self.lmin = [float(l[:, 0].min()) for l in self.lat]
+        self.alive = np.ones(self.n, dtype=bool)
+        self.t = 0.0
+        self.round = 0
+        self.next_order = 1
+        self.model = np.full(self.n, -1, dtype=np.int32)
+        self.round_of = np.full(self.n, -1, dtype=np.int32)
+        self.order_of = np.zeros(self.n, dtype=np.int32)
+        self.util = np.zeros(self.n, dtype=np.float64)
+        self.finish = np.zeros(self.n, dtype=np.float64)
+        self.log = []
+
+    # -- who can still be served -------------------------------------------
+    def live_queue(self, a):
+        """Live requests of application a in service order."""
+        ids = self.order[a]
+        ids = ids[self.alive[ids]]
+        dead = is_dead(int(self.p.penalty[a]), self.D[ids], self.t + self.lmin[a])
+        return ids[~dead]
+
+    def candidate_window(self, a):
+        return self.live_queue(a)[: int(self.p.max_batch)]
+
+    # -- candidate scores ----------------------------------------------------
+    def score_cube(self):
+        """Score[a, m, b-1] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
+        over the first b live requests of a; -inf where (a,m,b) is not a candidate."""
+        A, B = int(self.p.n_apps), int(self.p.max_batch)
+        m_max = int(np.max(self.p.n_models))
+        cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
+        for a in range(A):
+            q = self.candidate_window(a)
+            nb = q.shape[0]
+            if nb == 0:
+                continue
+            kind = int(self.p.penalty[a])
+            for m in range(int(self.p.n_models[a])):
+                for b in range(1, nb + 1):
+                    e = self.t + self.lat[a][m, b - 1]
+                    members = q[:b]
+                    terms = self.key[members] * utility(self.ea[members, m], kind, self.D[members], e)
+                    cube[a, m, b - 1] = terms.sum()
+        return cube
+
+    def score_cube_fast(self):
+        """Same numbers as score_cube with the (b, j) triangle done as one
+        masked array per (a, m); kept beside the loop version so that a test
+        can check one against the other."""
+        A, B = int(self.p.n_apps), int(self.p.max_batch)
+        m_max = int(np.max(self.p.n_models))
+        cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
+        for a in range(A):
+            q = self.candidate_window(a)
+            nb = q.shape[0]
+            if nb == 0:
+                continue
+            kind = int(self.p.penalty[a])
+            tri = np.tril(np.ones((nb, nb), dtype=bool))          # [b, j]: j <= b
+            for m in range(int(self.p.n_models[a])):
+                e = self.t + self.lat[a][m, :nb]                   # [b]
+                u = utility(self.ea[q, m][None, :], kind, self.D[q][None, :], e[:, None])
+                terms = np.where(tri, self.key[q][None, :] * u, 0.0)
+                cube[a, m, :nb] = terms.sum(axis=1)
+        return cube
+
+    def decide(self, cube=None):
+        """arg max over (a, m, b); exact ties go to the smallest (a, m, b).
+        Returns None when no application has a live request."""
+        if cube is None:
+            cube = self.score_cube_fast()
+        if not np.isfinite(cube).any():
+            return None
+        flat = int(np.argmax(cube))            # first maximum in C order = smallest (a,m,b)
+        a, m, bi = np.unravel_index(flat, cube.shape)
+        b = int(bi) + 1
+        ids = self.candidate_window(int(a))[:b]
+        return {"app": int(a), "model": int(m), "batch": b, "score": float(cube[a, m, bi]),
+                "ids": ids.copy(), "t_start": self.t, "t_end": self.t + self.lat[int(a)][int(m), bi]}
+
+    # -- commit ---------------------------------------------------------------
+    def commit(self, a, m, ids):
+        """Serve requests `ids` of application a as one batch on variant m."""
+        ids = np.asarray(ids, dtype=np.int64)
+        b = int(ids.shape[0])
+        assert 1 <= b <= int(self.p.max_batch)
+        assert np.all(self.app[ids] == a) and np.all(self.alive[ids])
+        t_end = self.t + self.lat[a][m, b - 1]
+        u = utility(self.ea[ids, m], int(self.p.penalty[a]), self.D[ids], t_end)
+        self.model[ids] = m
+        self.round_of[ids] = self.round
+        self.order_of[ids] = np.arange(self.next_order, self.next_order + b)
+        self.util[ids] = u
+        self.finish[ids] = t_end
+        self.alive[ids] = False
+        rec = {"app": a, "model": m, "batch": b, "round": self.round, "t_start": self.t, "t_end": t_end,
+               "batch_utility": float((self.w[ids] * u).sum()), "ids": ids.copy()}
+        self.log.append(rec)
+        self.next_order += b
+        self.round += 1
+        self.t = t_end
+        return rec
+
+    def step(self):
+        d = self.decide()
+        if d is None:
+            return None
+        rec = self.commit(d["app"], d["model"], d["ids"])
+        rec["score"] = d["score"]
+        return rec
+
+    def run(self, max_rounds=0):
+        """Greedy rounds until nothing is live (or max_rounds > 0 is reached)."""
+        while max_rounds <= 0 or self.round < max_rounds:
+            if self.step() is None:
+                break
+        return self.summary()
+
+    def summary(self):
+        done = self.model >= 0
+        viol = np.maximum(0.0, self.finish[done] - self.D[done])
+        return {"total_weighted_utility": float((self.w * self.util).sum()),
+                "mean_utility": float(self.util.sum() / self.n) if self.n else 0.0,
+                "total_violation_ms": float(viol.sum()),
+                "n_rounds": int(self.round), "n_scheduled": int(done.sum()),
+                "n_dropped": int(self.n - done.sum())}
