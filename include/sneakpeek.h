@@ -1,0 +1,191 @@
+/*
+ * sneakpeek.h -- C ABI of the MI355X (gfx950) SneakPeek scoring / batch-aware
+ * greedy scheduling library.
+ *
+ * The library scores every pending inference request against every model
+ * variant of its application and turns the queue into a schedule by greedy
+ * batch-selection rounds:
+ *
+ *   posterior      theta_i = softmax(f_{a_i}(x_i))            (Def. 4.1.1, 4.1.2)
+ *   data-aware EA  EA[i,m] = sum_c theta_ic * Acc[a_i][m][c]  (Sec. 4.1, eq. (9))
+ *   priority key   k_i = w_i (1 + Var_m EA[i,.]) exp(-D_i/T_d) (Sec. 5.1.1, eq. (12))
+ *   utility        u = EA * (1 - gamma_a(D, t + L[a][m][b]))   (Sec. 3.1, eq. (2); Sec. 6.1)
+ *   round          arg max over (a, m, b) of the key-weighted utility of the
+ *                  first b live requests of a in key order   (eq. (13), Alg. 1)
+ *
+ * All entry points are plain C: opaque context, plain pointers and sizes.
+ * Pointers named *_dev are DEVICE pointers owned by the caller (any HIP
+ * allocation on the context's device); all others are HOST pointers.  No call
+ * throws or aborts; every call returns an sp_status (or void).  Outputs are
+ * left untouched when a call fails before launching work.  A context serves
+ * one scheduling window at a time and must not be used from two threads at
+ * once; different contexts are independent.
+ */
+#ifndef SNEAKPEEK_H
+#define SNEAKPEEK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sp_ctx sp_ctx;
+
+typedef enum {
+  SP_OK = 0,
+  SP_DONE = 1,        /* no live request is left: not an error                   */
+  SP_EINVAL = -1,     /* bad argument, bad profile, or bad request data          */
+  SP_ENOMEM = -2,     /* host or device allocation failed                        */
+  SP_EDEVICE = -3,    /* a HIP call failed (see sp_last_hip_error)               */
+  SP_ESTATE = -4,     /* call order: rounds before any sp_score                  */
+  SP_ECAPACITY = -5   /* a size exceeds what the context or library supports     */
+} sp_status;
+
+/* Deadline penalties of Sec. 6.1, with x = (e - d) / d for completion e and
+ * relative deadline d; all are 0 for e <= d and capped at 1:
+ *   step    1                          linear   min(1, x)
+ *   sigmoid x^3 / (x^3 + (1-x)^3) for x < 1, else 1                           */
+typedef enum { SP_PEN_STEP = 0, SP_PEN_LINEAR = 1, SP_PEN_SIGMOID = 2 } sp_penalty;
+
+typedef enum { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
+
+/* Library limits (SP_ECAPACITY beyond them). */
+#define SP_MAX_MODELS 16      /* variants per application                        */
+#define SP_MAX_BATCH 256      /* largest batch size B                            */
+#define SP_MAX_APPS 65535
+
+/*
+ * Registered applications (Sec. 2.2 "System Model", Sec. 3.2): per
+ * application a SneakPeek head, the per-class accuracy (recall) of every
+ * model variant "for every possible target label", and each variant's
+ * profiled latency per batch size.  HOST pointers; sp_create copies
+ * everything, the caller keeps ownership.
+ *
+ * Head of application a: hidden_dim == 0 -> logistic, z = x W1 + b1 with
+ * W1 [feat_dim, C_a]; otherwise z = relu(x W1 + b1) W2 + b2 with
+ * W1 [feat_dim, hidden_dim], W2 [hidden_dim, C_a].  All matrices row-major.
+ * W1/W2 (and the request features) hold feat_dtype elements (float, or
+ * bfloat16 bit patterns in uint16_t); biases and tables are float.
+ */
+typedef struct {
+  int32_t n_apps;               /* A >= 1                                          */
+  int32_t feat_dim;             /* d >= 1                                          */
+  int32_t hidden_dim;           /* H >= 0                                          */
+  int32_t max_batch;            /* B: batch sizes are 1..B                         */
+  int32_t feat_dtype;           /* sp_dtype                                        */
+  int32_t max_requests;         /* capacity of the window buffers (>= 0)           */
+  const int32_t* n_classes;     /* [A] C_a >= 1                                    */
+  const int32_t* n_models;      /* [A] 1 <= M_a <= SP_MAX_MODELS                   */
+  const void* const* W1;        /* [A] -> [d, H] or [d, C_a]                       */
+  const float* const* b1;       /* [A] -> [H] or [C_a]                             */
+  const void* const* W2;        /* [A] -> [H, C_a]; NULL when hidden_dim == 0      */
+  const float* const* b2;       /* [A] -> [C_a];    NULL when hidden_dim == 0      */
+  const float* const* acc;      /* [A] -> [M_a, C_a], each in [0, 1]               */
+  const float* const* lat_ms;   /* [A] -> [M_a, B], >= 0, non-decreasing in b      */
+  const int32_t* penalty;       /* [A] sp_penalty (penalties are per application)  */
+  float prio_timescale_ms;      /* T_d > 0 of the priority key (1000 = seconds)    */
+} sp_profile;
+
+/* One committed batch.  Times are milliseconds on the worker clock, 0 at the
+ * start of the window (eq. (1) with the batch as the unit).                    */
+typedef struct {
+  int32_t app, model, batch, round;
+  double t_start_ms, t_end_ms;
+  float score;                  /* sum over members of key * utility               */
+  float batch_utility;          /* sum over members of weight * utility            */
+} sp_decision;
+
+typedef struct {
+  double total_weighted_utility;   /* sum_i w_i u_i                                */
+  double mean_utility;             /* (1/N) sum_i u_i, the objective of eq. (3)    */
+  double total_violation_ms;       /* sum over served requests of max(0, e_i - D_i)*/
+  int32_t n_rounds, n_scheduled, n_dropped;
+  int32_t done;                    /* 1 when no live request is left               */
+} sp_summary;
+
+/* What sp_debug_dump can export (parity tests only; not on the hot path). */
+typedef enum {
+  SP_DUMP_ORDER = 0,      /* int32 [n]: request ids in service order, application-major      */
+  SP_DUMP_SEGMENTS = 1,   /* int32 [A+1]: start of each application's range in that order    */
+  SP_DUMP_SCORE_CUBE = 2, /* float [A, SP_MAX_MODELS? no: Mmax, B]: Score at the current clock,
+                             -1 where (a, m, b) is not a candidate                            */
+  SP_DUMP_LOGITS = 3      /* float [n, Cmax]: head outputs z_i (0 beyond C_a)                 */
+} sp_dump_kind;
+
+/* Validate and upload a profile to `device_id`, allocate window buffers for
+ * max_requests.  SP_EINVAL: NULL pointers, counts out of range, acc outside
+ * [0,1] or NaN, latency negative / NaN / decreasing in b, unknown enum,
+ * T_d <= 0.  SP_ECAPACITY: beyond the SP_MAX_* limits.  On success *out owns
+ * device memory until sp_destroy.                                              */
+sp_status sp_create(const sp_profile* profile, int device_id, sp_ctx** out);
+void sp_destroy(sp_ctx* ctx);
+
+/* Scoring pass over one window of n pending requests (Sec. 3.2: requests are
+ * enqueued during a window, then scheduled together): groups requests by
+ * application, computes EA and the priority key of every request, orders each
+ * application's requests by (key descending, request id ascending) and resets
+ * the window state (everyone pending, clock 0, round 0).
+ *   x_dev            [n, feat_dim] row-major, feat_dtype elements
+ *   app_dev          [n] application id in [0, A)
+ *   deadline_ms_dev  [n] D_i = d_i - now, > 0
+ *   weight_dev       [n] w_i >= 0 (all ones recovers the paper's priority)
+ *   ea_out_dev       [n, Mmax] (Mmax = max_a M_a; 0 beyond M_a) or NULL
+ *   key_out_dev      [n] or NULL
+ * Work is enqueued on `stream` (a hipStream_t, NULL = default stream) and the
+ * call returns without waiting.  The inputs may be freed once the stream has
+ * passed this call.  n == 0 is legal.  n > max_requests -> SP_ECAPACITY.  Bad
+ * request data (application id out of range, deadline <= 0 or NaN, weight < 0
+ * or NaN) is detected on the device and reported as SP_EINVAL by the next
+ * sp_greedy_round / sp_schedule; such a window is not scheduled.              */
+sp_status sp_score(sp_ctx* ctx, int32_t n, const void* x_dev, const int32_t* app_dev,
+                   const float* deadline_ms_dev, const float* weight_dev, void* stream,
+                   float* ea_out_dev, float* key_out_dev);
+
+/* One greedy round at the current clock t: a request is live while pending
+ * and its penalty on the earliest possible completion t + min_m L[a][m][1] is
+ * below 1; for every application the first min(B, n_live) live requests in
+ * service order form the candidate window; every (a, m, b) is scored and the
+ * best one is committed (exact ties: smallest (a, m, b)); the clock advances
+ * to its completion time.  Waits for the stream.  *out_host receives the
+ * decision; req_ids_out_dev (NULL or [B]) the ids of its members in service
+ * order.  Returns SP_DONE (and leaves *out_host untouched) when no request is
+ * live, SP_ESTATE before the first sp_score.                                   */
+sp_status sp_greedy_round(sp_ctx* ctx, void* stream, sp_decision* out_host, int32_t* req_ids_out_dev);
+
+/* Greedy rounds until nothing is live, or until max_rounds more rounds have
+ * been committed (max_rounds <= 0: no limit).  Rounds run back to back on the
+ * device; the call waits for the stream before returning.
+ *   model_out_dev / round_out_dev / order_out_dev / util_out_dev: each NULL
+ *     or [n]; variant id (-1 = not served), round id (-1), global execution
+ *     order starting at 1 (0 = not served, as s_ij = 0 in Sec. 3.1), utility.
+ *   round_log_host [log_capacity]: decisions of all rounds of this window so
+ *     far (including earlier sp_greedy_round calls), truncated to capacity.
+ *   out_host: totals over the window so far.
+ * Returns SP_OK when stopped by max_rounds, SP_DONE when the queue is
+ * exhausted (both fill the outputs).                                           */
+sp_status sp_schedule(sp_ctx* ctx, int32_t max_rounds, void* stream,
+                      int32_t* model_out_dev, int32_t* round_out_dev, int32_t* order_out_dev,
+                      float* util_out_dev, sp_decision* round_log_host, int32_t log_capacity,
+                      sp_summary* out_host);
+
+/* Parity-test export; waits for the stream.  SP_DUMP_LOGITS recomputes the
+ * heads from x_dev/app_dev (pass the same arrays as to sp_score); the other
+ * kinds ignore them.  dst_dev must hold the size listed at sp_dump_kind.       */
+sp_status sp_debug_dump(sp_ctx* ctx, int32_t kind, void* stream, const void* x_dev,
+                        const int32_t* app_dev, void* dst_dev);
+
+/* Mean device time of the kernels of the last sp_score / sp_schedule call is
+ * not measured here: time with events on the stream you pass in.              */
+
+const char* sp_strerror(sp_status s);
+/* Text of the last HIP error seen by this context (empty string if none). */
+const char* sp_last_hip_error(const sp_ctx* ctx);
+/* max_a M_a and max_a C_a of the profile (row widths of the outputs). */
+int32_t sp_max_models(const sp_ctx* ctx);
+int32_t sp_max_classes(const sp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNEAKPEEK_H */

@@ -1,0 +1,525 @@
+// Host runtime and C ABI of the SneakPeek HIP library: profile validation and
+// upload, window buffers, kernel launch order, status codes.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "sneakpeek.h"
+#include "sp_common.h"
+#include "sp_rounds.h"
+#include "sp_score_generic.h"
+#include "sp_sort.h"
+
+using namespace sp;
+
+static_assert(sizeof(Decision) == sizeof(sp_decision), "device and ABI decision records must match");
+static_assert(SP_MAX_MODELS == kMaxModels && SP_MAX_BATCH == kMaxBatch, "limits out of sync");
+
+struct sp_ctx {
+  int device = 0;
+  Tables tb{};
+  Window w{};
+  std::vector<void*> dev_allocs;
+  int A = 0, d = 0, H = 0, B = 0, Mmax = 0, Cmax = 0, dtype = 0;
+  int64_t cap = 0;
+  uint32_t* bufK[2] = {nullptr, nullptr};
+  int32_t* bufV[2] = {nullptr, nullptr};
+  uint32_t* hist = nullptr;
+  int64_t hist_units = 0;
+  int32_t* seg1 = nullptr;    // [2] single-segment plan for the application pass
+  int32_t* unit1 = nullptr;   // [2]
+  State* h_state = nullptr;   // pinned mirror
+  bool scored = false;
+  int32_t n = 0;
+  int32_t rounds_done = 0;
+  bool done = false;
+  size_t score_lds = 0;
+  std::string hip_err;
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    if (prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+#define SP_HIP(ctx, call)                                                          \
+  do {                                                                             \
+    hipError_t e_ = (call);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      (ctx)->hip_err = std::string(#call) + ": " + hipGetErrorString(e_);          \
+      return SP_EDEVICE;                                                           \
+    }                                                                              \
+  } while (0)
+
+template <typename T>
+sp_status dev_alloc(sp_ctx* c, T** out, size_t count) {
+  void* p = nullptr;
+  size_t bytes = (count ? count : 1) * sizeof(T);
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    c->hip_err = std::string("hipMalloc: ") + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? SP_ENOMEM : SP_EDEVICE;
+  }
+  c->dev_allocs.push_back(p);
+  *out = (T*)p;
+  return SP_OK;
+}
+
+template <typename T>
+sp_status dev_upload(sp_ctx* c, T** out, const std::vector<T>& host) {
+  sp_status s = dev_alloc(c, out, host.size());
+  if (s != SP_OK) return s;
+  if (!host.empty()) SP_HIP(c, hipMemcpy(*out, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  return SP_OK;
+}
+
+int unit_size_for(int64_t n) {
+  int64_t s = ((n / 512 + 63) / 64) * 64;
+  if (s < 256) s = 256;
+  if (s > 4096) s = 4096;
+  return (int)s;
+}
+
+int app_passes(int A) { return (A + 1 <= 256) ? 1 : ((A + 1 <= 65536) ? 2 : 3); }
+
+sp_status validate_profile(const sp_profile* p) {
+  if (!p || !p->n_classes || !p->n_models || !p->W1 || !p->b1 || !p->acc || !p->lat_ms || !p->penalty)
+    return SP_EINVAL;
+  if (p->n_apps < 1 || p->feat_dim < 1 || p->hidden_dim < 0 || p->max_batch < 1 || p->max_requests < 0)
+    return SP_EINVAL;
+  if (p->feat_dtype != SP_F32 && p->feat_dtype != SP_BF16) return SP_EINVAL;
+  if (!(p->prio_timescale_ms > 0.f) || !std::isfinite(p->prio_timescale_ms)) return SP_EINVAL;
+  if (p->hidden_dim > 0 && (!p->W2 || !p->b2)) return SP_EINVAL;
+  if (p->n_apps > SP_MAX_APPS || p->max_batch > SP_MAX_BATCH) return SP_ECAPACITY;
+  for (int a = 0; a < p->n_apps; ++a) {
+    const int C = p->n_classes[a], M = p->n_models[a];
+    if (C < 1 || M < 1) return SP_EINVAL;
+    if (M > SP_MAX_MODELS) return SP_ECAPACITY;
+    if (!p->W1[a] || !p->b1[a] || !p->acc[a] || !p->lat_ms[a]) return SP_EINVAL;
+    if (p->hidden_dim > 0 && (!p->W2[a] || !p->b2[a])) return SP_EINVAL;
+    if (p->penalty[a] < SP_PEN_STEP || p->penalty[a] > SP_PEN_SIGMOID) return SP_EINVAL;
+    for (int i = 0; i < M * C; ++i) {
+      const float v = p->acc[a][i];
+      if (!(v >= 0.f && v <= 1.f)) return SP_EINVAL;
+    }
+    for (int m = 0; m < M; ++m)
+      for (int b = 0; b < p->max_batch; ++b) {
+        const float v = p->lat_ms[a][m * p->max_batch + b];
+        if (!(v >= 0.f) || !std::isfinite(v)) return SP_EINVAL;
+        if (b > 0 && v < p->lat_ms[a][m * p->max_batch + b - 1]) return SP_EINVAL;
+      }
+  }
+  return SP_OK;
+}
+
+template <typename T>
+sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
+  const int A = p->n_apps, d = p->feat_dim, H = p->hidden_dim;
+  std::vector<T> W1, W2;
+  std::vector<float> b1, b2;
+  std::vector<int64_t> W1o(A), W2o(A, 0);
+  std::vector<int32_t> b1o(A), b2o(A, 0);
+  for (int a = 0; a < A; ++a) {
+    const int C = p->n_classes[a];
+    const int out1 = H > 0 ? H : C;
+    W1o[a] = (int64_t)W1.size();
+    b1o[a] = (int32_t)b1.size();
+    const T* w1 = (const T*)p->W1[a];
+    W1.insert(W1.end(), w1, w1 + (size_t)d * out1);
+    b1.insert(b1.end(), p->b1[a], p->b1[a] + out1);
+    if (H > 0) {
+      W2o[a] = (int64_t)W2.size();
+      b2o[a] = (int32_t)b2.size();
+      const T* w2 = (const T*)p->W2[a];
+      W2.insert(W2.end(), w2, w2 + (size_t)H * C);
+      b2.insert(b2.end(), p->b2[a], p->b2[a] + C);
+    }
+  }
+  sp_status s;
+  T *dW1, *dW2;
+  float *db1, *db2;
+  int64_t *dW1o, *dW2o;
+  int32_t *db1o, *db2o;
+  if ((s = dev_upload(c, &dW1, W1)) != SP_OK) return s;
+  if ((s = dev_upload(c, &dW2, W2)) != SP_OK) return s;
+  if ((s = dev_upload(c, &db1, b1)) != SP_OK) return s;
+  if ((s = dev_upload(c, &db2, b2)) != SP_OK) return s;
+  if ((s = dev_upload(c, &dW1o, W1o)) != SP_OK) return s;
+  if ((s = dev_upload(c, &dW2o, W2o)) != SP_OK) return s;
+  if ((s = dev_upload(c, &db1o, b1o)) != SP_OK) return s;
+  if ((s = dev_upload(c, &db2o, b2o)) != SP_OK) return s;
+  c->tb.W1 = dW1; c->tb.W2 = dW2; c->tb.b1 = db1; c->tb.b2 = db2;
+  c->tb.W1_off = dW1o; c->tb.W2_off = dW2o; c->tb.b1_off = db1o; c->tb.b2_off = db2o;
+  return SP_OK;
+}
+
+sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
+  const int A = p->n_apps, B = p->max_batch;
+  c->A = A; c->d = p->feat_dim; c->H = p->hidden_dim; c->B = B; c->dtype = p->feat_dtype;
+  c->cap = p->max_requests;
+  int Mmax = 0, Cmax = 0;
+  for (int a = 0; a < A; ++a) {
+    Mmax = std::max(Mmax, p->n_models[a]);
+    Cmax = std::max(Cmax, p->n_classes[a]);
+  }
+  c->Mmax = Mmax; c->Cmax = Cmax;
+  c->score_lds = (size_t)kScoreWaves * kScoreRW * (size_t)(c->d + c->H) * sizeof(float);
+  if (c->score_lds > 160 * 1024) return SP_ECAPACITY;
+
+  Tables& tb = c->tb;
+  tb.A = A; tb.d = c->d; tb.H = c->H; tb.B = B; tb.Mmax = Mmax; tb.Cmax = Cmax; tb.dtype = c->dtype;
+  tb.inv_timescale = 1.0f / p->prio_timescale_ms;
+  sp_status s;
+  std::vector<int32_t> ncls(p->n_classes, p->n_classes + A), nmod(p->n_models, p->n_models + A),
+      pen(p->penalty, p->penalty + A), acc_off(A);
+  std::vector<float> acc, lat((size_t)A * Mmax * B, 0.f), lmin(A);
+  for (int a = 0; a < A; ++a) {
+    const int C = ncls[a], M = nmod[a];
+    acc_off[a] = (int32_t)acc.size();
+    acc.insert(acc.end(), p->acc[a], p->acc[a] + (size_t)M * C);
+    float lm = p->lat_ms[a][0];
+    for (int m = 0; m < M; ++m) {
+      lm = std::min(lm, p->lat_ms[a][m * B]);
+      for (int b = 0; b < B; ++b) lat[((size_t)a * Mmax + m) * B + b] = p->lat_ms[a][m * B + b];
+    }
+    lmin[a] = lm;
+  }
+  int32_t *d_ncls, *d_nmod, *d_pen, *d_acc_off;
+  float *d_acc, *d_lat, *d_lmin;
+  if ((s = dev_upload(c, &d_ncls, ncls)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_nmod, nmod)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_pen, pen)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_acc_off, acc_off)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_acc, acc)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_lat, lat)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_lmin, lmin)) != SP_OK) return s;
+  tb.n_classes = d_ncls; tb.n_models = d_nmod; tb.penalty = d_pen; tb.acc_off = d_acc_off;
+  tb.acc = d_acc; tb.lat = d_lat; tb.lmin = d_lmin;
+  s = (c->dtype == SP_BF16) ? upload_heads<uint16_t>(c, p) : upload_heads<float>(c, p);
+  if (s != SP_OK) return s;
+
+  // window buffers
+  const size_t N = (size_t)c->cap;
+  Window& w = c->w;
+  if ((s = dev_alloc(c, &w.seg, A + 2)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.tile_start, A + 1)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.unit_start, A + 1)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.ea, N * Mmax)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.key, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.D_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.w_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.key_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.alive_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.head, 2 * (size_t)A)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.model, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.round_of, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.order_of, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.util, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.cand, (size_t)A * Mmax)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.win_pos, (size_t)A * B)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.win_n, A)) != SP_OK) return s;
+  w.log_cap = (int32_t)std::max<size_t>(N, 1);
+  if ((s = dev_alloc(c, &w.log, (size_t)w.log_cap)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.last_ids, B)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.st, 1)) != SP_OK) return s;
+  for (int i = 0; i < 2; ++i) {
+    if ((s = dev_alloc(c, &c->bufK[i], N)) != SP_OK) return s;
+    if ((s = dev_alloc(c, &c->bufV[i], N)) != SP_OK) return s;
+  }
+  c->hist_units = (int64_t)std::max<size_t>(512, N / 256) + A + 8;
+  if ((s = dev_alloc(c, &c->hist, (size_t)c->hist_units * 256)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->seg1, 2)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->unit1, 2)) != SP_OK) return s;
+  SP_HIP(c, hipHostMalloc((void**)&c->h_state, sizeof(State), hipHostMallocDefault));
+  std::memset(c->h_state, 0, sizeof(State));
+  SP_HIP(c, hipMemset(w.st, 0, sizeof(State)));
+  if (c->score_lds > 64 * 1024) {
+    const int bytes = (int)c->score_lds;
+#define SP_SET_LDS(T, MT) \
+    SP_HIP(c, hipFuncSetAttribute((const void*)k_score_generic<T, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
+    SP_SET_LDS(float, 4); SP_SET_LDS(float, 8); SP_SET_LDS(float, 16);
+    SP_SET_LDS(uint16_t, 4); SP_SET_LDS(uint16_t, 8); SP_SET_LDS(uint16_t, 16);
+#undef SP_SET_LDS
+  }
+  return SP_OK;
+}
+
+template <typename T>
+void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, const int32_t* ids, const float* D,
+                          const float* wt, uint32_t* sortkey, float* logits) {
+  const dim3 blk(kScoreWaves * kWave);
+  if (c->Mmax <= 4)
+    hipLaunchKernelGGL((k_score_generic<T, 4>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+  else if (c->Mmax <= 8)
+    hipLaunchKernelGGL((k_score_generic<T, 8>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+  else
+    hipLaunchKernelGGL((k_score_generic<T, 16>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+}
+
+void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
+                  uint32_t* sortkey, float* logits) {
+  const int grid = (c->n + kScoreTile - 1) / kScoreTile + c->A;
+  if (c->dtype == SP_BF16)
+    launch_score_generic<uint16_t>(c, s, grid, x, ids, D, wt, sortkey, logits);
+  else
+    launch_score_generic<float>(c, s, grid, x, ids, D, wt, sortkey, logits);
+}
+
+// One stable radix pass; (keys, vals) -> (keys_out, vals_out).
+void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, const uint32_t* keys,
+                const int32_t* vals, int shift, uint32_t* keys_out, int32_t* vals_out) {
+  const int blocks = (max_units + kSortWaves - 1) / kSortWaves;
+  hipLaunchKernelGGL(k_radix_hist, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, shift, c->hist);
+  hipLaunchKernelGGL(k_radix_scan, dim3(plan.nseg), dim3(256), 0, s, plan, c->hist);
+  hipLaunchKernelGGL(k_radix_scatter, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, vals, shift,
+                     (const uint32_t*)c->hist, keys_out, vals_out);
+}
+
+void launch_round(sp_ctx* c, hipStream_t s, int32_t* ids_out, float* cube) {
+  hipLaunchKernelGGL(k_round_score, dim3(c->A * c->Mmax), dim3(kRoundThreads), 0, s, c->tb, c->w, cube);
+  if (cube == nullptr)
+    hipLaunchKernelGGL(k_round_commit, dim3(1), dim3(kRoundThreads), 0, s, c->tb, c->w, ids_out);
+}
+
+sp_status fetch_state(sp_ctx* c, hipStream_t s) {
+  SP_HIP(c, hipMemcpyAsync(c->h_state, c->w.st, sizeof(State), hipMemcpyDeviceToHost, s));
+  SP_HIP(c, hipStreamSynchronize(s));
+  SP_HIP(c, hipGetLastError());
+  c->rounds_done = c->h_state->round;
+  c->done = c->h_state->done != 0;
+  return c->h_state->err ? SP_EINVAL : SP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sp_status sp_create(const sp_profile* profile, int device_id, sp_ctx** out) {
+  if (!out) return SP_EINVAL;
+  *out = nullptr;
+  sp_status s = validate_profile(profile);
+  if (s != SP_OK) return s;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) return SP_EDEVICE;
+  sp_ctx* c = new (std::nothrow) sp_ctx();
+  if (!c) return SP_ENOMEM;
+  c->device = device_id;
+  DeviceGuard g(device_id);
+  if (!g.ok) {
+    delete c;
+    return SP_EDEVICE;
+  }
+  s = build_ctx(c, profile);
+  if (s != SP_OK) {
+    sp_destroy(c);
+    return s;
+  }
+  *out = c;
+  return SP_OK;
+}
+
+void sp_destroy(sp_ctx* c) {
+  if (!c) return;
+  DeviceGuard g(c->device);
+  (void)hipDeviceSynchronize();
+  for (void* p : c->dev_allocs) (void)hipFree(p);
+  if (c->h_state) (void)hipHostFree(c->h_state);
+  delete c;
+}
+
+sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_dev, const float* deadline_ms_dev,
+                   const float* weight_dev, void* stream, float* ea_out_dev, float* key_out_dev) {
+  if (!c || n < 0) return SP_EINVAL;
+  if (n > 0 && (!x_dev || !app_dev || !deadline_ms_dev || !weight_dev)) return SP_EINVAL;
+  if ((int64_t)n > c->cap) return SP_ECAPACITY;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  Window& w = c->w;
+  w.n = n;
+  c->n = n;
+  c->rounds_done = 0;
+  c->done = false;
+  const int A = c->A;
+  hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(64), 0, s, w.st);
+
+  uint32_t *curK = c->bufK[0], *altK = c->bufK[1];
+  int32_t *curV = c->bufV[0], *altV = c->bufV[1];
+  const int unit = unit_size_for(n);
+  if (n > 0) {
+    // requests grouped by application: stable pass(es) over the application id
+    hipLaunchKernelGGL(k_app_keys, dim3((n + 255) / 256), dim3(256), 0, s, n, app_dev, A, curK, w.st);
+    hipLaunchKernelGGL(k_single_segment, dim3(1), dim3(64), 0, s, n, unit, c->seg1, c->unit1);
+    SortPlan whole{c->seg1, c->unit1, 1, unit};
+    const int units1 = (n + unit - 1) / unit;
+    const int32_t* vin = nullptr;
+    for (int p = 0; p < app_passes(A); ++p) {
+      radix_pass(c, s, whole, units1, curK, vin, 8 * p, altK, altV);
+      std::swap(curK, altK);
+      std::swap(curV, altV);
+      vin = curV;
+    }
+  }
+  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, kScoreTile, unit, w.seg,
+                     w.tile_start, w.unit_start, w.head);
+  if (n > 0) {
+    // posterior -> EA -> key, one pass over the features
+    uint32_t* sortkey = altK;
+    launch_score(c, s, x_dev, curV, deadline_ms_dev, weight_dev, sortkey, nullptr);
+    // service order: inside each application by (key descending, id ascending)
+    const int32_t* ids_all = curV;
+    SortPlan per_app{w.seg, w.unit_start, A, unit};
+    const int units2 = (n + unit - 1) / unit + A;
+    uint32_t *k_in = sortkey, *k_out = curK;
+    int32_t *v_in = curV, *v_out = altV;
+    for (int p = 0; p < 4; ++p) {
+      radix_pass(c, s, per_app, units2, k_in, v_in, 8 * p, k_out, v_out);
+      std::swap(k_in, k_out);
+      std::swap(v_in, v_out);
+    }
+    // four passes: the result is back in the buffer the application pass wrote,
+    // whose tail (requests with an invalid application) was never touched
+    w.id_s = v_in;
+    hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg,
+                       (const int32_t*)v_in, ids_all, deadline_ms_dev, weight_dev, w);
+    if (ea_out_dev)
+      SP_HIP(c, hipMemcpyAsync(ea_out_dev, w.ea, (size_t)n * c->Mmax * sizeof(float), hipMemcpyDeviceToDevice, s));
+    if (key_out_dev)
+      SP_HIP(c, hipMemcpyAsync(key_out_dev, w.key, (size_t)n * sizeof(float), hipMemcpyDeviceToDevice, s));
+  }
+  SP_HIP(c, hipGetLastError());
+  c->scored = true;
+  return SP_OK;
+}
+
+sp_status sp_greedy_round(sp_ctx* c, void* stream, sp_decision* out_host, int32_t* req_ids_out_dev) {
+  if (!c) return SP_EINVAL;
+  if (!c->scored) return SP_ESTATE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  const int32_t before = c->rounds_done;
+  launch_round(c, s, req_ids_out_dev, nullptr);
+  sp_status st = fetch_state(c, s);
+  if (st != SP_OK) return st;
+  if (c->rounds_done == before) return SP_DONE;
+  if (out_host) std::memcpy(out_host, &c->h_state->last, sizeof(sp_decision));
+  return SP_OK;
+}
+
+sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* model_out_dev, int32_t* round_out_dev,
+                      int32_t* order_out_dev, float* util_out_dev, sp_decision* round_log_host,
+                      int32_t log_capacity, sp_summary* out_host) {
+  if (!c || log_capacity < 0 || (log_capacity > 0 && !round_log_host)) return SP_EINVAL;
+  if (!c->scored) return SP_ESTATE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  const int32_t start = c->rounds_done;
+  sp_status st = SP_OK;
+  bool fetched = false;
+  while (!c->done) {
+    int chunk = 64;
+    if (max_rounds > 0) chunk = std::min(chunk, start + max_rounds - c->rounds_done);
+    if (chunk <= 0) break;
+    for (int i = 0; i < chunk; ++i) launch_round(c, s, nullptr, nullptr);
+    st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
+    fetched = true;
+    if (st != SP_OK) return st;
+  }
+  if (!fetched && (st = fetch_state(c, s)) != SP_OK) return st;
+  const size_t n = (size_t)c->n;
+  if (n > 0) {
+    if (model_out_dev) SP_HIP(c, hipMemcpyAsync(model_out_dev, c->w.model, n * 4, hipMemcpyDeviceToDevice, s));
+    if (round_out_dev) SP_HIP(c, hipMemcpyAsync(round_out_dev, c->w.round_of, n * 4, hipMemcpyDeviceToDevice, s));
+    if (order_out_dev) SP_HIP(c, hipMemcpyAsync(order_out_dev, c->w.order_of, n * 4, hipMemcpyDeviceToDevice, s));
+    if (util_out_dev) SP_HIP(c, hipMemcpyAsync(util_out_dev, c->w.util, n * 4, hipMemcpyDeviceToDevice, s));
+  }
+  const int32_t n_log = std::min(std::min(c->rounds_done, log_capacity), c->w.log_cap);
+  if (n_log > 0)
+    SP_HIP(c, hipMemcpyAsync(round_log_host, c->w.log, (size_t)n_log * sizeof(sp_decision), hipMemcpyDeviceToHost, s));
+  SP_HIP(c, hipStreamSynchronize(s));
+  if (out_host) {
+    const State& h = *c->h_state;
+    out_host->total_weighted_utility = h.total_wu;
+    out_host->mean_utility = c->n > 0 ? h.total_u / (double)c->n : 0.0;
+    out_host->total_violation_ms = h.total_viol;
+    out_host->n_rounds = h.round;
+    out_host->n_scheduled = h.n_sched;
+    out_host->n_dropped = c->n - h.n_sched;
+    out_host->done = h.done;
+  }
+  return c->done ? SP_DONE : SP_OK;
+}
+
+sp_status sp_debug_dump(sp_ctx* c, int32_t kind, void* stream, const void* x_dev, const int32_t* app_dev,
+                        void* dst_dev) {
+  (void)app_dev;
+  if (!c || !dst_dev) return SP_EINVAL;
+  if (!c->scored) return SP_ESTATE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t n = (size_t)c->n;
+  switch (kind) {
+    case SP_DUMP_ORDER:
+      if (n) SP_HIP(c, hipMemcpyAsync(dst_dev, c->w.id_s, n * 4, hipMemcpyDeviceToDevice, s));
+      break;
+    case SP_DUMP_SEGMENTS:
+      SP_HIP(c, hipMemcpyAsync(dst_dev, c->w.seg, (size_t)(c->A + 1) * 4, hipMemcpyDeviceToDevice, s));
+      break;
+    case SP_DUMP_SCORE_CUBE: {
+      const int64_t cnt = (int64_t)c->A * c->Mmax * c->B;
+      hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, (float*)dst_dev, cnt, -1.0f);
+      launch_round(c, s, nullptr, (float*)dst_dev);
+      break;
+    }
+    case SP_DUMP_LOGITS: {
+      if (n == 0) break;
+      if (!x_dev) return SP_EINVAL;
+      const int64_t cnt = (int64_t)n * c->Cmax;
+      hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, (float*)dst_dev, cnt, 0.0f);
+      // same kernel as the scoring pass, with the EA / key epilogue switched off
+      launch_score(c, s, x_dev, c->w.id_s, nullptr, nullptr, nullptr, (float*)dst_dev);
+      break;
+    }
+    default:
+      return SP_EINVAL;
+  }
+  SP_HIP(c, hipStreamSynchronize(s));
+  SP_HIP(c, hipGetLastError());
+  return SP_OK;
+}
+
+const char* sp_strerror(sp_status s) {
+  switch (s) {
+    case SP_OK: return "ok";
+    case SP_DONE: return "no live request left";
+    case SP_EINVAL: return "invalid argument, profile or request data";
+    case SP_ENOMEM: return "out of memory";
+    case SP_EDEVICE: return "HIP call failed";
+    case SP_ESTATE: return "call order: score the window first";
+    case SP_ECAPACITY: return "size beyond the context's or the library's capacity";
+  }
+  return "unknown status";
+}
+
+const char* sp_last_hip_error(const sp_ctx* c) { return c ? c->hip_err.c_str() : ""; }
+int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
+int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Shared device-side declarations of the SneakPeek HIP library (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sp {
+
+constexpr int kMaxModels = 16;   // variants per application
+constexpr int kMaxBatch = 256;   // largest batch size
+constexpr int kWave = 64;
+
+// error bits raised by kernels on bad request data
+constexpr uint32_t kErrApp = 1u;
+constexpr uint32_t kErrDeadline = 2u;
+constexpr uint32_t kErrWeight = 4u;
+
+// Immutable per-context tables (device pointers).
+struct Tables {
+  int32_t A, d, H, B, Mmax, Cmax, dtype;
+  float inv_timescale;
+  const int32_t* n_classes;   // [A]
+  const int32_t* n_models;    // [A]
+  const int32_t* penalty;     // [A]
+  const void* W1;             // concatenated per-app matrices, feat_dtype
+  const int64_t* W1_off;      // [A] element offsets
+  const float* b1;
+  const int32_t* b1_off;      // [A]
+  const void* W2;
+  const int64_t* W2_off;
+  const float* b2;
+  const int32_t* b2_off;
+  const float* acc;           // per app [M_a, C_a]
+  const int32_t* acc_off;     // [A]
+  const float* lat;           // [A, Mmax, B]
+  const float* lmin;          // [A] min_m L[a][m][1]
+};
+
+struct Decision {             // mirrors sp_decision
+  int32_t app, model, batch, round;
+  double t_start, t_end;
+  float score, batch_utility;
+};
+
+// Scalars of the running window, one instance in device memory.
+struct State {
+  double t;                   // worker clock, ms since window start
+  double total_wu;            // sum w*u over served requests
+  double total_u;             // sum u
+  double total_viol;          // sum max(0, e - D)
+  int32_t round;              // rounds committed so far
+  int32_t next_order;         // next global execution order (starts at 1)
+  int32_t n_sched;
+  int32_t done;               // 1 once a round found nothing live
+  uint32_t err;               // kErr* bits
+  int32_t pad;
+  Decision last;              // the most recent committed batch
+};
+
+// Mutable window buffers (device pointers).
+struct Window {
+  int32_t n;
+  int32_t* seg;               // [A+2] start of each app's range in service order; seg[A] = #valid, seg[A+1] = n
+  int32_t* tile_start;        // [A+1] prefix of scoring tiles
+  int32_t* unit_start;        // [A+1] prefix of sort units
+  float* ea;                  // [n, Mmax]
+  float* key;                 // [n]
+  int32_t* id_s;              // [n] request id at each service position
+  float* D_s;                 // [n]
+  float* w_s;                 // [n]
+  float* key_s;               // [n]
+  uint8_t* alive_s;           // [n] 1 = pending
+  int32_t* head;              // [2, A] first position that may still be live (double-buffered by round parity)
+  int32_t* model;             // [n] outputs, indexed by request id
+  int32_t* round_of;          // [n]
+  int32_t* order_of;          // [n]
+  float* util;                // [n]
+  unsigned long long* cand;   // [A, Mmax] best packed candidate per (a, m) of the running round
+  int32_t* win_pos;           // [A, B] service positions of each app's candidate window
+  int32_t* win_n;             // [A]
+  Decision* log;              // [log_cap]
+  int32_t log_cap;
+  int32_t* last_ids;          // [B] members of the last committed batch
+  State* st;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_as_float(const T* p, int64_t i);
+template <> __device__ __forceinline__ float load_as_float<float>(const float* p, int64_t i) { return p[i]; }
+template <> __device__ __forceinline__ float load_as_float<uint16_t>(const uint16_t* p, int64_t i) {
+  return bf16_bits_to_float(p[i]);
+}
+
+// 1 - gamma_a(D, E) of Sec. 6.1 with the clock kept in double so that the
+// comparisons E > D and E >= 2D are exact and the small remainders 2D - E and
+// E - D lose nothing to cancellation.  kind: 0 step, 1 linear, 2 sigmoid.
+// With x = (E-D)/D and y = 1 - x = (2D-E)/D: linear 1 - x = y; sigmoid
+// 1 - x^3/(x^3+y^3) = y^3/(x^3+y^3); x + y = 1 keeps the denominator >= 1/4.
+__device__ __forceinline__ float one_minus_penalty(int kind, float D, float invD, double E) {
+  double Dd = (double)D;
+  if (E <= Dd) return 1.0f;
+  if (kind == 0) return 0.0f;
+  double rem = 2.0 * Dd - E;
+  if (rem <= 0.0) return 0.0f;
+  float y = (float)rem * invD;
+  if (kind == 1) return y;
+  float x = (float)(E - Dd) * invD;
+  float y3 = y * y * y, x3 = x * x * x;
+  return y3 / (x3 + y3);
+}
+
+// dead: penalty already 1 on the earliest possible completion E0.
+__device__ __forceinline__ bool is_dead(int kind, float D, double E0) {
+  double Dd = (double)D;
+  return kind == 0 ? (E0 > Dd) : (E0 >= 2.0 * Dd);
+}
+
+}  // namespace sp

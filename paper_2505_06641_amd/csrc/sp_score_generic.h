@@ -1,0 +1,186 @@
+// Scoring kernel for arbitrary head shapes (any d, H, C; M <= 16; fp32 or bf16
+// inputs, fp32 arithmetic).  One wavefront owns RW requests of one application
+// from the features to EA and the priority key; lanes span hidden units, then
+// classes.  The posterior is never written: each lane keeps an online-softmax
+// state (running max, running sum of exponentials, M running sums of
+// exp * Acc[m][c]) over the classes it visits, and the 64 lane states are
+// merged once per request (Def. 4.1.2 posterior; Sec. 4.1 eq. (9); Sec. 5.1.1
+// eq. (12)).
+#pragma once
+#include "sp_common.h"
+
+namespace sp {
+
+constexpr int kScoreWaves = 4;
+constexpr int kScoreRW = 8;                          // requests per wavefront
+constexpr int kScoreTile = kScoreWaves * kScoreRW;   // requests per workgroup
+
+// Find s with start[s] <= v < start[s+1] (start has nseg+1 entries, non-decreasing).
+__device__ __forceinline__ int find_segment(const int32_t* start, int nseg, int v) {
+  int lo = 0, hi = nseg;
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (start[mid] <= v) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// EA row -> population variance -> key; also the order-preserving sort key.
+// Called by one lane per request.
+template <int MT>
+__device__ __forceinline__ void finish_request(const Tables& tb, const Window& w, int pos, int id, int M,
+                                               const float (&ea)[MT], const float* D, const float* wt,
+                                               uint32_t* sortkey) {
+  float mean = 0.f;
+#pragma unroll
+  for (int m = 0; m < MT; ++m) mean += (m < M) ? ea[m] : 0.f;
+  mean /= (float)M;
+  float var = 0.f;
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    float dv = ea[m] - mean;
+    var += (m < M) ? dv * dv : 0.f;
+  }
+  var /= (float)M;
+  float Di = D[id], wi = wt[id];
+  uint32_t err = 0;
+  if (!(Di > 0.f)) err |= kErrDeadline;
+  if (!(wi >= 0.f)) err |= kErrWeight;
+  if (err) atomicOr(&w.st->err, err);
+  float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
+  w.key[id] = key;
+  sortkey[pos] = ~__float_as_uint(key);
+  float* row = w.ea + (int64_t)id * tb.Mmax;
+  for (int m = 0; m < tb.Mmax; ++m) {
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < MT; ++q) v = (q == m && q < M) ? ea[q] : v;
+    row[m] = v;
+  }
+}
+
+template <typename T, int MT>
+__global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
+    Tables tb, Window w, const T* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ D,
+    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, float* __restrict__ logits_out) {
+  constexpr int RW = kScoreRW;
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tile = blockIdx.x;
+  if (tile >= w.tile_start[tb.A]) return;
+  const int a = find_segment(w.tile_start, tb.A, tile);
+  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
+  const int p0 = seg_b + (tile - w.tile_start[a]) * kScoreTile + wave * RW;   // first service position of this wave
+  const int nr = min(RW, seg_e - p0);                                          // may be <= 0
+  const int d = tb.d, H = tb.H, C = tb.n_classes[a], M = tb.n_models[a];
+  float* xs = lds + (size_t)wave * RW * (d + H);
+  float* hs = xs + (size_t)RW * d;
+
+  // stage this wave's feature rows as float
+  for (int r = 0; r < RW; ++r) {
+    if (r < nr) {
+      const T* row = x + (int64_t)ids[p0 + r] * d;
+      for (int k = lane; k < d; k += 64) xs[r * d + k] = load_as_float<T>(row, k);
+    } else {
+      for (int k = lane; k < d; k += 64) xs[r * d + k] = 0.f;
+    }
+  }
+  __syncthreads();
+
+  const float* in = xs;
+  int K = d;
+  const T* Wout = (const T*)tb.W1 + tb.W1_off[a];
+  const float* bout = tb.b1 + tb.b1_off[a];
+  if (H > 0) {
+    const T* W1 = Wout;
+    const float* b1 = bout;
+    for (int j0 = 0; j0 < H; j0 += 64) {
+      const int j = j0 + lane;
+      const bool ok = j < H;
+      float acc[RW];
+      const float bj = ok ? b1[j] : 0.f;
+#pragma unroll
+      for (int r = 0; r < RW; ++r) acc[r] = bj;
+      for (int k = 0; k < d; ++k) {
+        const float wv = ok ? load_as_float<T>(W1, (int64_t)k * H + j) : 0.f;
+#pragma unroll
+        for (int r = 0; r < RW; ++r) acc[r] = fmaf(xs[r * d + k], wv, acc[r]);
+      }
+      if (ok) {
+#pragma unroll
+        for (int r = 0; r < RW; ++r) hs[r * H + j] = fmaxf(acc[r], 0.f);
+      }
+    }
+    __syncthreads();
+    in = hs;
+    K = H;
+    Wout = (const T*)tb.W2 + tb.W2_off[a];
+    bout = tb.b2 + tb.b2_off[a];
+  }
+
+  // classes: lanes stride over c; online softmax state per (lane, request)
+  constexpr float kNegBig = -1e30f;
+  float mx[RW], sm[RW], ea[RW][MT];
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    mx[r] = kNegBig;
+    sm[r] = 0.f;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) ea[r][m] = 0.f;
+  }
+  const float* acc_a = tb.acc + tb.acc_off[a];
+  for (int c0 = 0; c0 < C; c0 += 64) {
+    const int c = c0 + lane;
+    const bool ok = c < C;
+    float z[RW];
+    const float bc = ok ? bout[c] : 0.f;
+#pragma unroll
+    for (int r = 0; r < RW; ++r) z[r] = bc;
+    for (int k = 0; k < K; ++k) {
+      const float wv = ok ? load_as_float<T>(Wout, (int64_t)k * C + c) : 0.f;
+#pragma unroll
+      for (int r = 0; r < RW; ++r) z[r] = fmaf(in[r * K + k], wv, z[r]);
+    }
+    if (ok) {
+      float ac[MT];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) ac[m] = (m < M) ? acc_a[m * C + c] : 0.f;
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        if (logits_out != nullptr && r < nr) logits_out[(int64_t)ids[p0 + r] * tb.Cmax + c] = z[r];
+        const float mn = fmaxf(mx[r], z[r]);
+        const float sc = expf(mx[r] - mn);
+        const float p = expf(z[r] - mn);
+        sm[r] = sm[r] * sc + p;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) ea[r][m] = fmaf(p, ac[m], ea[r][m] * sc);
+        mx[r] = mn;
+      }
+    }
+  }
+
+  // merge the 64 lane states of each request
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const float mt = wave_max(mx[r]);
+    const float f = expf(mx[r] - mt);
+    const float st = wave_sum(sm[r] * f);
+    float row[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) row[m] = wave_sum(ea[r][m] * f) / st;
+    if (lane == 0 && r < nr && logits_out == nullptr) finish_request<MT>(tb, w, p0 + r, ids[p0 + r], M, row, D, wt, sortkey);
+  }
+}
+
+}  // namespace sp

@@ -1,0 +1,208 @@
+// Stable least-significant-digit radix passes (8-bit digits) over (key, value)
+// pairs, run independently inside each segment of the array.  Used twice per
+// window: once over the whole queue with the application id as the key (the
+// request groups of Alg. 1, "HashMap<app : request list>"), then four times
+// inside each application's range with the inverted bits of the priority key
+// (Alg. 1, "requests in g sorted by priority"; eq. (12)).
+//
+// The unit of work is one wavefront walking `unit` consecutive elements of one
+// segment 64 at a time, in order; units never straddle segments.  A pass is
+// three kernels: per-unit digit histograms, one scan per segment in
+// (digit, unit) order, and the scatter, in which every wavefront ranks its 64
+// elements per digit with ballots (equal digits keep their order) and bumps a
+// wavefront-private running offset table in LDS.  No inter-workgroup waiting.
+#pragma once
+#include "sp_common.h"
+#include "sp_score_generic.h"   // find_segment
+
+namespace sp {
+
+constexpr int kSortWaves = 4;
+
+struct SortPlan {
+  const int32_t* seg;          // [nseg+1] segment starts
+  const int32_t* unit_start;   // [nseg+1] prefix of units per segment
+  int32_t nseg;
+  int32_t unit;                // elements per unit, multiple of 64
+};
+
+// Orders this wavefront's LDS accesses around it (compiler fence; the hardware
+// already runs one wavefront's LDS operations in issue order).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// mask of lanes whose 8-bit digit equals mine
+__device__ __forceinline__ unsigned long long match_digit(uint32_t digit, bool valid) {
+  unsigned long long m = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const bool bit = (digit >> b) & 1u;
+    const unsigned long long vote = __ballot(bit);
+    m &= bit ? vote : ~vote;
+  }
+  return m;
+}
+
+__device__ __forceinline__ bool unit_range(const SortPlan& sp, int u, int& beg, int& end) {
+  if (u >= sp.unit_start[sp.nseg]) return false;
+  const int s = find_segment(sp.unit_start, sp.nseg, u);
+  beg = sp.seg[s] + (u - sp.unit_start[s]) * sp.unit;
+  end = min(beg + sp.unit, sp.seg[s + 1]);
+  return true;
+}
+
+// Clamp application ids into [0, A] (A = "invalid") and flag bad ones.
+__global__ void k_app_keys(int n, const int32_t* __restrict__ app, int A, uint32_t* __restrict__ keys, State* st) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int a = app[i];
+  const bool ok = a >= 0 && a < A;
+  keys[i] = ok ? (uint32_t)a : (uint32_t)A;
+  if (!ok) atomicOr(&st->err, kErrApp);
+}
+
+// The whole queue as one segment.
+__global__ void k_single_segment(int n, int unit, int32_t* seg, int32_t* unit_start) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    seg[0] = 0;
+    seg[1] = n;
+    unit_start[0] = 0;
+    unit_start[1] = (n + unit - 1) / unit;
+  }
+}
+
+__global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, const uint32_t* __restrict__ keys,
+                                                                  int shift, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t cnt[kSortWaves][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = lane; i < 256; i += 64) cnt[wave][i] = 0;
+  wave_sync();
+  const int u = blockIdx.x * kSortWaves + wave;
+  int beg = 0, end = 0;
+  const bool have = unit_range(sp, u, beg, end);
+  if (have) {
+    for (int i = beg + lane; i < end; i += 64) atomicAdd(&cnt[wave][(keys[i] >> shift) & 255u], 1u);
+    wave_sync();
+    for (int i = lane; i < 256; i += 64) hist[(int64_t)u * 256 + i] = cnt[wave][i];
+  }
+}
+
+// One workgroup of 256 threads per segment; thread = digit.  Turns the
+// per-unit counts into destination offsets: order (digit, unit), base seg[s].
+__global__ __launch_bounds__(256) void k_radix_scan(SortPlan sp, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t tot[256];
+  const int s = blockIdx.x, dgt = threadIdx.x;
+  const int u0 = sp.unit_start[s], u1 = sp.unit_start[s + 1];
+  uint32_t sum = 0;
+  for (int u = u0; u < u1; ++u) sum += hist[(int64_t)u * 256 + dgt];
+  tot[dgt] = sum;
+  __syncthreads();
+  // exclusive scan over the 256 digit totals (Hillis-Steele in LDS)
+  for (int o = 1; o < 256; o <<= 1) {
+    const uint32_t v = (dgt >= o) ? tot[dgt - o] : 0u;
+    __syncthreads();
+    tot[dgt] += v;
+    __syncthreads();
+  }
+  uint32_t run = (uint32_t)sp.seg[s] + tot[dgt] - sum;
+  for (int u = u0; u < u1; ++u) {
+    const uint32_t c = hist[(int64_t)u * 256 + dgt];
+    hist[(int64_t)u * 256 + dgt] = run;
+    run += c;
+  }
+}
+
+// vals_in == nullptr means the identity (value = element index).
+__global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
+    SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift,
+    const uint32_t* __restrict__ offs, uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
+  __shared__ uint32_t run[kSortWaves][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u = blockIdx.x * kSortWaves + wave;
+  int beg = 0, end = 0;
+  const bool have = unit_range(sp, u, beg, end);
+  if (!have) return;   // no block-wide barrier below: wavefronts are independent
+  for (int i = lane; i < 256; i += 64) run[wave][i] = offs[(int64_t)u * 256 + i];
+  wave_sync();
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int base = beg; base < end; base += 64) {
+    const int i = base + lane;
+    const bool valid = i < end;
+    const uint32_t key = valid ? keys_in[i] : 0u;
+    const int32_t val = valid ? (vals_in ? vals_in[i] : i) : 0;
+    const uint32_t dg = (key >> shift) & 255u;
+    const unsigned long long same = match_digit(dg, valid);
+    const int rank = __popcll(same & lt);
+    // the first lane of each digit group reserves the group's slots, then hands the base to its group
+    const int leader = valid ? (__ffsll((long long)same) - 1) : lane;
+    uint32_t base_off = 0;
+    if (valid && lane == leader) base_off = atomicAdd(&run[wave][dg], (uint32_t)__popcll(same));
+    base_off = __shfl(base_off, leader);
+    const uint32_t dst = base_off + (uint32_t)rank;
+    if (valid) {
+      keys_out[dst] = key;
+      vals_out[dst] = val;
+    }
+  }
+}
+
+// Segment starts from the application-sorted keys (values in [0, A], A =
+// invalid): seg[a] = first position with key >= a; then the prefixes of
+// scoring tiles and sort units per application.  One workgroup.
+__global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
+                                                  int tile, int unit, int32_t* seg, int32_t* tile_start,
+                                                  int32_t* unit_start, int32_t* head) {
+  for (int a = threadIdx.x; a <= A + 1; a += blockDim.x) {
+    int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (sorted_app[mid] < (uint32_t)a) lo = mid + 1; else hi = mid;
+    }
+    seg[a] = lo;                            // seg[A] = number of valid requests, seg[A+1] = n
+  }
+  __syncthreads();
+  for (int a = threadIdx.x; a < A; a += blockDim.x) {
+    head[a] = seg[a];
+    head[A + a] = seg[a];
+  }
+  if (threadIdx.x == 0) {
+    int ts = 0, us = 0;
+    for (int a = 0; a < A; ++a) {
+      tile_start[a] = ts;
+      unit_start[a] = us;
+      const int na = seg[a + 1] - seg[a];
+      ts += (na + tile - 1) / tile;
+      us += (na + unit - 1) / unit;
+    }
+    tile_start[A] = ts;
+    unit_start[A] = us;
+  }
+}
+
+// After the last pass: per service position the request id, deadline, weight
+// and key; and the per-request outputs reset to "not served".
+__global__ void k_finish_order(int n, int n_valid_at /*index into seg*/, const int32_t* __restrict__ seg,
+                               const int32_t* __restrict__ ids_valid, const int32_t* __restrict__ ids_all,
+                               const float* __restrict__ D, const float* __restrict__ wt, Window w) {
+  const int pos = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pos >= n) return;
+  const int nv = seg[n_valid_at];
+  const int id = pos < nv ? ids_valid[pos] : ids_all[pos];
+  if (pos < nv) {
+    w.id_s[pos] = id;
+    w.D_s[pos] = D[id];
+    w.w_s[pos] = wt[id];
+    w.key_s[pos] = w.key[id];
+    w.alive_s[pos] = 1;
+  } else {
+    w.alive_s[pos] = 0;
+  }
+  w.model[id] = -1;
+  w.round_of[id] = -1;
+  w.order_of[id] = 0;
+  w.util[id] = 0.f;
+}
+
+}  // namespace sp
