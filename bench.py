@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the SneakPeek scoring + greedy-round hot path on one MI355X.
+
+A step is one pass of the whole path over one window of synthetic requests:
+sp_score (group by application, posterior -> expected accuracy -> priority
+key, per-application ordering) followed by sp_schedule (greedy rounds).
+Inputs are resident in HBM before the timed region.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+METRIC = "request x model x batch candidates scored/s"
+
+# published MI355X peaks used for the roofline fractions
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_VALU_F32_TFLOPS = 157.3
+
+
+def scoring_flops_per_request(p, a):
+    """Algorithmic flops of the head and the EA contraction for one request of application a."""
+    d, H, C, M = int(p.feat_dim), int(p.hidden_dim), int(p.n_classes[a]), int(p.n_models[a])
+    head = 2 * d * C if H == 0 else 2 * (d * H + H * C)
+    return head + 2 * C * M
+
+
+def cpu_baseline(w, n_sample, rounds):
+    """The oracle, as it stands, on the first n_sample requests of the same workload."""
+    from oracle import sneakpeek_oracle as orc
+    from paper_2505_06641_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rq = w.requests
+    sub = wl.Requests(x=rq.x[:n_sample], app=rq.app[:n_sample], deadline_rel_ms=rq.deadline_rel_ms[:n_sample],
+                      weight=rq.weight[:n_sample])
+    t0 = time.perf_counter()
+    ea, key = orc.score_requests(w.profile, sub)
+    t1 = time.perf_counter()
+    win = orc.Window(w.profile, sub, ea=ea, key=key)
+    win.run(max_rounds=rounds)
+    t2 = time.perf_counter()
+    p = w.profile
+    cand = float(n_sample) * int(np.max(p.n_models)) * int(p.max_batch)
+    return {"value": cand / (t2 - t0), "unit": "candidates/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n_sample} of {rq.n} requests of {w.name} (full profile), scoring {t1 - t0:.2f} s + "
+                      f"{win.round} rounds {t2 - t1:.2f} s, NumPy float64",
+            "round_latency_us": (t2 - t1) / max(1, win.round) * 1e6}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by application, see DESIGN.md); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_06641_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = wl.make(args.workload)
+    p, rq = w.profile, w.requests
+    n, A = rq.n, int(p.n_apps)
+    m_max, B = int(np.max(p.n_models)), int(p.max_batch)
+    rounds = w.rounds                      # <= 0: until the queue is exhausted
+    ctx = binding.Context(p, n)
+    x, app, D, wt = binding.to_device(rq)
+    model = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    rnd = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    order = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    util = torch.empty(n, device="cuda:0")
+    ctx.sp_set_timing(True)
+
+    def step():
+        ctx.sp_score(x, app, D, wt)
+        return ctx.sp_schedule(rounds, model, rnd, order, util, log_capacity=0)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    k_ms, group_ms, order_ms, rounds_ms, round_us = [], [], [], [], []
+    n_rounds = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rc, summ, _ = step()
+        tm = ctx.sp_get_timing()           # waits only for events that the step has already waited for
+        k_ms.append(tm["score_kernel_ms"]); group_ms.append(tm["group_ms"])
+        order_ms.append(tm["order_ms"]); rounds_ms.append(tm["rounds_ms"])
+        n_rounds = summ["n_rounds"]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_round = [v * 1e3 for v in ctx.sp_get_round_times()][:max(1, n_rounds)]
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    cand = float(n) * m_max * B
+    value = cand / (ms_per_step * 1e-3)
+
+    counts = np.bincount(rq.app, minlength=A)
+    flops = float(sum(int(counts[a]) * scoring_flops_per_request(p, a) for a in range(A)))
+    k_avg = float(np.mean(k_ms))
+    elem = 2 if p.feat_dtype == wl.BF16 else 4
+    k_bytes = float(n) * (int(p.feat_dim) * elem + m_max * 4 + 4 + 4 + 8)   # x row in; EA row, key, sort key out; D, w in
+    tflops = flops / (k_avg * 1e-3) / 1e12
+    gbs = k_bytes / (k_avg * 1e-3) / 1e9
+    ai = flops / k_bytes
+    if p.feat_dtype == wl.BF16:
+        peak_c, ridge = PEAK_MFMA_BF16_TFLOPS, PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    else:
+        peak_c, ridge = PEAK_MFMA_F32_TFLOPS, PEAK_MFMA_F32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if ai >= ridge:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": peak_c, "unit": "TFLOP/s", "frac": tflops / peak_c}
+    else:
+        roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": None,
+                 "algorithmic_flops": flops, "algorithmic_bytes": k_bytes, "hbm_gbs": gbs, "tflops": tflops})
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if p.feat_dtype == wl.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {A} applications, C={int(np.max(p.n_classes))}, M={m_max}, B={B}, "
+                               f"N={n}, d={int(p.feat_dim)}, H={int(p.hidden_dim)}, seed {w.seed}; "
+                               f"one scoring pass + {'greedy rounds until exhausted' if rounds <= 0 else str(rounds) + ' greedy rounds'}",
+                   "n_requests": n, "rounds_run": n_rounds},
+        "greedy_round_latency_us": {"mean": float(np.mean(per_round)) if per_round else None,
+                                    "p50": float(np.percentile(per_round, 50)) if per_round else None,
+                                    "p99": float(np.percentile(per_round, 99)) if per_round else None,
+                                    "rounds": len(per_round)},
+        "stage_ms": {"group_by_app": float(np.mean(group_ms)), "score_kernel": k_avg,
+                     "order_by_key": float(np.mean(order_ms)), "rounds": float(np.mean(rounds_ms))},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 16384, "cfg5": 131072}[args.workload]
+        ns = min(n, args.cpu_sample or default_sample)
+        out["cpu_baseline"] = cpu_baseline(w, ns, rounds)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -106,12 +106,22 @@ typedef struct {
 
 /* What sp_debug_dump can export (parity tests only; not on the hot path). */
 typedef enum {
-  SP_DUMP_ORDER = 0,      /* int32 [n]: request ids in service order, application-major      */
-  SP_DUMP_SEGMENTS = 1,   /* int32 [A+1]: start of each application's range in that order    */
-  SP_DUMP_SCORE_CUBE = 2, /* float [A, SP_MAX_MODELS? no: Mmax, B]: Score at the current clock,
-                             -1 where (a, m, b) is not a candidate                            */
-  SP_DUMP_LOGITS = 3      /* float [n, Cmax]: head outputs z_i (0 beyond C_a)                 */
+  SP_DUMP_ORDER = 0,      /* int32 [n]: request ids in service order, application-major        */
+  SP_DUMP_SEGMENTS = 1,   /* int32 [A+1]: start of each application's range in that order      */
+  SP_DUMP_SCORE_CUBE = 2, /* float [A, Mmax, B]: Score[a][m][b-1] at the current clock, -1
+                             where (a, m, b) is not a candidate                                 */
+  SP_DUMP_LOGITS = 3      /* float [n, Cmax]: head outputs z_i (0 beyond C_a)                   */
 } sp_dump_kind;
+
+/* Device times of the last sp_score / sp_schedule call, from HIP events that
+ * the library records on the caller's stream while timing is enabled.         */
+typedef struct {
+  float group_ms;          /* grouping requests by application                                 */
+  float score_kernel_ms;   /* the fused posterior / EA / key kernel alone (one launch)         */
+  float order_ms;          /* per-application ordering by key                                  */
+  float rounds_ms;         /* all rounds of the last sp_schedule call                          */
+  int32_t n_rounds_timed;  /* rounds with an individual time (see sp_get_round_times)          */
+} sp_timing;
 
 /* Validate and upload a profile to `device_id`, allocate window buffers for
  * max_requests.  SP_EINVAL: NULL pointers, counts out of range, acc outside
@@ -175,8 +185,15 @@ sp_status sp_schedule(sp_ctx* ctx, int32_t max_rounds, void* stream,
 sp_status sp_debug_dump(sp_ctx* ctx, int32_t kind, void* stream, const void* x_dev,
                         const int32_t* app_dev, void* dst_dev);
 
-/* Mean device time of the kernels of the last sp_score / sp_schedule call is
- * not measured here: time with events on the stream you pass in.              */
+/* Benchmark aid.  sp_set_timing(ctx, 1) makes sp_score and sp_schedule record
+ * HIP events around their stages (and after each of the first 4096 rounds);
+ * sp_get_timing / sp_get_round_times wait for those events and return the
+ * elapsed device times (per-round times in milliseconds, HOST array of
+ * `capacity` floats, *n_out = number written).  SP_ESTATE if timing is off or
+ * nothing has been recorded yet.                                              */
+sp_status sp_set_timing(sp_ctx* ctx, int32_t enable);
+sp_status sp_get_timing(sp_ctx* ctx, sp_timing* out_host);
+sp_status sp_get_round_times(sp_ctx* ctx, float* ms_out_host, int32_t capacity, int32_t* n_out);
 
 const char* sp_strerror(sp_status s);
 /* Text of the last HIP error seen by this context (empty string if none). */

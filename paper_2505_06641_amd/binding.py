@@ -20,7 +20,8 @@ SP_EINVAL, SP_ENOMEM, SP_EDEVICE, SP_ESTATE, SP_ECAPACITY = -1, -2, -3, -4, -5
 SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
-           "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes"]
+           "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
+           "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
 class sp_profile(C.Structure):
@@ -48,6 +49,14 @@ class sp_summary(C.Structure):
     _fields_ = [("total_weighted_utility", C.c_double), ("mean_utility", C.c_double),
                 ("total_violation_ms", C.c_double), ("n_rounds", C.c_int32), ("n_scheduled", C.c_int32),
                 ("n_dropped", C.c_int32), ("done", C.c_int32)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class sp_timing(C.Structure):
+    _fields_ = [("group_ms", C.c_float), ("score_kernel_ms", C.c_float), ("order_ms", C.c_float),
+                ("rounds_ms", C.c_float), ("n_rounds_timed", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -88,6 +97,12 @@ def load_library(path: Optional[str] = None):
     lib.sp_max_models.restype = C.c_int32
     lib.sp_max_classes.argtypes = [vp]
     lib.sp_max_classes.restype = C.c_int32
+    lib.sp_set_timing.argtypes = [vp, C.c_int32]
+    lib.sp_set_timing.restype = C.c_int
+    lib.sp_get_timing.argtypes = [vp, C.POINTER(sp_timing)]
+    lib.sp_get_timing.restype = C.c_int
+    lib.sp_get_round_times.argtypes = [vp, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
+    lib.sp_get_round_times.restype = C.c_int
     if path is None:
         _lib = lib
     return lib
@@ -217,6 +232,20 @@ class Context:
         self._check(rc, "sp_schedule", ok=(SP_OK, SP_DONE))
         n_log = min(sm.n_rounds, log_capacity)
         return rc, sm.as_dict(), [log[i].as_dict() for i in range(n_log)]
+
+    def sp_set_timing(self, enable=True):
+        return self._check(self.lib.sp_set_timing(self.h, 1 if enable else 0), "sp_set_timing")
+
+    def sp_get_timing(self):
+        t = sp_timing()
+        self._check(self.lib.sp_get_timing(self.h, C.byref(t)), "sp_get_timing")
+        return t.as_dict()
+
+    def sp_get_round_times(self, capacity=4096):
+        buf = (C.c_float * capacity)()
+        n = C.c_int32(0)
+        self._check(self.lib.sp_get_round_times(self.h, buf, capacity, C.byref(n)), "sp_get_round_times")
+        return [buf[i] for i in range(n.value)]
 
     def sp_debug_dump(self, kind, dst, x=None, app=None, stream=None):
         rc = self.lib.sp_debug_dump(self.h, int(kind), _stream_ptr(stream), _dptr(x), _dptr(app), _dptr(dst))

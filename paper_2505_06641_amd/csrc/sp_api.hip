@@ -40,7 +40,15 @@ struct sp_ctx {
   bool done = false;
   size_t score_lds = 0;
   std::string hip_err;
+  // optional stage timing (benchmarks)
+  bool timing = false;
+  bool timed_score = false, timed_rounds = false;
+  hipEvent_t ev[6] = {};                 // group start, score start, score stop, order stop, rounds start, rounds stop
+  std::vector<hipEvent_t> round_ev;      // one after each timed round
+  int n_round_ev = 0;
 };
+
+constexpr int kMaxRoundEvents = 4096;
 
 namespace {
 
@@ -338,6 +346,9 @@ void sp_destroy(sp_ctx* c) {
   (void)hipDeviceSynchronize();
   for (void* p : c->dev_allocs) (void)hipFree(p);
   if (c->h_state) (void)hipHostFree(c->h_state);
+  for (hipEvent_t e : c->ev)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->round_ev) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -356,6 +367,10 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   c->done = false;
   const int A = c->A;
   hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(64), 0, s, w.st);
+  const bool tm = c->timing && n > 0;
+  c->timed_score = false;
+  c->timed_rounds = false;
+  if (tm) SP_HIP(c, hipEventRecord(c->ev[0], s));
 
   uint32_t *curK = c->bufK[0], *altK = c->bufK[1];
   int32_t *curV = c->bufV[0], *altV = c->bufV[1];
@@ -379,7 +394,9 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;
+    if (tm) SP_HIP(c, hipEventRecord(c->ev[1], s));
     launch_score(c, s, x_dev, curV, deadline_ms_dev, weight_dev, sortkey, nullptr);
+    if (tm) SP_HIP(c, hipEventRecord(c->ev[2], s));
     // service order: inside each application by (key descending, id ascending)
     const int32_t* ids_all = curV;
     SortPlan per_app{w.seg, w.unit_start, A, unit};
@@ -396,6 +413,10 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     w.id_s = v_in;
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg,
                        (const int32_t*)v_in, ids_all, deadline_ms_dev, weight_dev, w);
+    if (tm) {
+      SP_HIP(c, hipEventRecord(c->ev[3], s));
+      c->timed_score = true;
+    }
     if (ea_out_dev)
       SP_HIP(c, hipMemcpyAsync(ea_out_dev, w.ea, (size_t)n * c->Mmax * sizeof(float), hipMemcpyDeviceToDevice, s));
     if (key_out_dev)
@@ -432,16 +453,25 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   const int32_t start = c->rounds_done;
   sp_status st = SP_OK;
   bool fetched = false;
+  const bool tm = c->timing;
+  c->n_round_ev = 0;
+  c->timed_rounds = false;
+  if (tm) SP_HIP(c, hipEventRecord(c->ev[4], s));
   while (!c->done) {
     int chunk = 64;
     if (max_rounds > 0) chunk = std::min(chunk, start + max_rounds - c->rounds_done);
     if (chunk <= 0) break;
-    for (int i = 0; i < chunk; ++i) launch_round(c, s, nullptr, nullptr);
+    for (int i = 0; i < chunk; ++i) {
+      launch_round(c, s, nullptr, nullptr);
+      if (tm && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
+    }
+    if (tm) SP_HIP(c, hipEventRecord(c->ev[5], s));
     st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
     fetched = true;
     if (st != SP_OK) return st;
   }
   if (!fetched && (st = fetch_state(c, s)) != SP_OK) return st;
+  c->timed_rounds = tm && fetched;
   const size_t n = (size_t)c->n;
   if (n > 0) {
     if (model_out_dev) SP_HIP(c, hipMemcpyAsync(model_out_dev, c->w.model, n * 4, hipMemcpyDeviceToDevice, s));
@@ -502,6 +532,55 @@ sp_status sp_debug_dump(sp_ctx* c, int32_t kind, void* stream, const void* x_dev
   }
   SP_HIP(c, hipStreamSynchronize(s));
   SP_HIP(c, hipGetLastError());
+  return SP_OK;
+}
+
+sp_status sp_set_timing(sp_ctx* c, int32_t enable) {
+  if (!c) return SP_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  if (enable && !c->ev[0]) {
+    for (hipEvent_t& e : c->ev) SP_HIP(c, hipEventCreate(&e));
+    c->round_ev.resize(kMaxRoundEvents);
+    for (hipEvent_t& e : c->round_ev) SP_HIP(c, hipEventCreate(&e));
+  }
+  c->timing = enable != 0;
+  c->timed_score = c->timed_rounds = false;
+  return SP_OK;
+}
+
+sp_status sp_get_timing(sp_ctx* c, sp_timing* out) {
+  if (!c || !out) return SP_EINVAL;
+  if (!c->timing || (!c->timed_score && !c->timed_rounds)) return SP_ESTATE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  sp_timing t{};
+  if (c->timed_score) {
+    SP_HIP(c, hipEventSynchronize(c->ev[3]));
+    SP_HIP(c, hipEventElapsedTime(&t.group_ms, c->ev[0], c->ev[1]));
+    SP_HIP(c, hipEventElapsedTime(&t.score_kernel_ms, c->ev[1], c->ev[2]));
+    SP_HIP(c, hipEventElapsedTime(&t.order_ms, c->ev[2], c->ev[3]));
+  }
+  if (c->timed_rounds) {
+    SP_HIP(c, hipEventSynchronize(c->ev[5]));
+    SP_HIP(c, hipEventElapsedTime(&t.rounds_ms, c->ev[4], c->ev[5]));
+    t.n_rounds_timed = c->n_round_ev;
+  }
+  *out = t;
+  return SP_OK;
+}
+
+sp_status sp_get_round_times(sp_ctx* c, float* ms_out, int32_t capacity, int32_t* n_out) {
+  if (!c || !n_out || capacity < 0 || (capacity > 0 && !ms_out)) return SP_EINVAL;
+  if (!c->timing || !c->timed_rounds) return SP_ESTATE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  const int n = std::min(capacity, c->n_round_ev);
+  for (int i = 0; i < n; ++i) {
+    SP_HIP(c, hipEventSynchronize(c->round_ev[i]));
+    SP_HIP(c, hipEventElapsedTime(&ms_out[i], i == 0 ? c->ev[4] : c->round_ev[i - 1], c->round_ev[i]));
+  }
+  *n_out = n;
   return SP_OK;
 }
 
