@@ -13,6 +13,7 @@
 #include "sp_common.h"
 #include "sp_rounds.h"
 #include "sp_score_generic.h"
+#include "sp_score_mfma.h"
 #include "sp_sort.h"
 
 using namespace sp;
@@ -39,6 +40,10 @@ struct sp_ctx {
   int32_t rounds_done = 0;
   bool done = false;
   size_t score_lds = 0;
+  int mfma_D = 0;             // > 0: logistic heads run on the matrix-core kernel with this padded feature width
+  float* blocks = nullptr;    // packed (application, class tile) blocks for that kernel
+  int64_t* block_off = nullptr;
+  size_t mfma_lds = 0;
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -175,6 +180,8 @@ sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
   return SP_OK;
 }
 
+sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p);
+
 sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   const int A = p->n_apps, B = p->max_batch;
   c->A = A; c->d = p->feat_dim; c->H = p->hidden_dim; c->B = B; c->dtype = p->feat_dtype;
@@ -219,6 +226,10 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   tb.acc = d_acc; tb.lat = d_lat; tb.lmin = d_lmin;
   s = (c->dtype == SP_BF16) ? upload_heads<uint16_t>(c, p) : upload_heads<float>(c, p);
   if (s != SP_OK) return s;
+  if (c->H == 0 && c->dtype == SP_F32 && c->d <= 256) {
+    c->mfma_D = c->d <= 64 ? 64 : (c->d <= 128 ? 128 : 256);
+    if ((s = pack_mfma_blocks(c, p)) != SP_OK) return s;
+  }
 
   // window buffers
   const size_t N = (size_t)c->cap;
@@ -266,6 +277,36 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   return SP_OK;
 }
 
+template <int D>
+sp_status pack_mfma_blocks_d(sp_ctx* c, const sp_profile* p) {
+  using LB = LogisticBlock<D>;
+  std::vector<int64_t> off(p->n_apps);
+  size_t total = 0;
+  for (int a = 0; a < p->n_apps; ++a) {
+    off[a] = (int64_t)total;
+    total += (size_t)((p->n_classes[a] + kClassTile - 1) / kClassTile) * LB::kFloats;
+  }
+  std::vector<float> host(total);
+  for (int a = 0; a < p->n_apps; ++a)
+    pack_logistic_blocks<D>((const float*)p->W1[a], p->b1[a], p->acc[a], p->feat_dim, p->n_classes[a],
+                            p->n_models[a], host.data() + off[a]);
+  sp_status s;
+  if ((s = dev_upload(c, &c->blocks, host)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->block_off, off)) != SP_OK) return s;
+  c->mfma_lds = 2 * (size_t)LB::kFloats * sizeof(float);
+  SP_HIP(c, hipFuncSetAttribute((const void*)k_score_logistic_mfma<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)c->mfma_lds));
+  return SP_OK;
+}
+
+sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p) {
+  switch (c->mfma_D) {
+    case 64: return pack_mfma_blocks_d<64>(c, p);
+    case 128: return pack_mfma_blocks_d<128>(c, p);
+    default: return pack_mfma_blocks_d<256>(c, p);
+  }
+}
+
 template <typename T>
 void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, const int32_t* ids, const float* D,
                           const float* wt, uint32_t* sortkey, float* logits) {
@@ -278,8 +319,22 @@ void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, con
     hipLaunchKernelGGL((k_score_generic<T, 16>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
 }
 
+int score_tile(const sp_ctx* c) { return c->mfma_D > 0 ? kMfTile : kScoreTile; }
+
 void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
                   uint32_t* sortkey, float* logits) {
+  if (c->mfma_D > 0) {
+    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
+    const dim3 blk(kMfThreads);
+#define SP_LAUNCH_MF(DD)                                                                                        \
+    hipLaunchKernelGGL((k_score_logistic_mfma<DD>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w, (const float*)x, \
+                       ids, D, wt, sortkey, (const float*)c->blocks, (const int64_t*)c->block_off, logits)
+    if (c->mfma_D == 64) SP_LAUNCH_MF(64);
+    else if (c->mfma_D == 128) SP_LAUNCH_MF(128);
+    else SP_LAUNCH_MF(256);
+#undef SP_LAUNCH_MF
+    return;
+  }
   const int grid = (c->n + kScoreTile - 1) / kScoreTile + c->A;
   if (c->dtype == SP_BF16)
     launch_score_generic<uint16_t>(c, s, grid, x, ids, D, wt, sortkey, logits);
@@ -389,7 +444,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       vin = curV;
     }
   }
-  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, kScoreTile, unit, w.seg,
+  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, score_tile(c), unit, w.seg,
                      w.tile_start, w.unit_start, w.head);
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
