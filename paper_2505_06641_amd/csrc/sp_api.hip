@@ -293,9 +293,7 @@ sp_status pack_mfma_blocks_d(sp_ctx* c, const sp_profile* p) {
   sp_status s;
   if ((s = dev_upload(c, &c->blocks, host)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->block_off, off)) != SP_OK) return s;
-  c->mfma_lds = 2 * (size_t)LB::kFloats * sizeof(float);
-  SP_HIP(c, hipFuncSetAttribute((const void*)k_score_logistic_mfma<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)c->mfma_lds));
+  c->mfma_lds = 0;   // the kernel's two block buffers are static LDS
   return SP_OK;
 }
 
@@ -326,9 +324,17 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
   if (c->mfma_D > 0) {
     const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
     const dim3 blk(kMfThreads);
-#define SP_LAUNCH_MF(DD)                                                                                        \
-    hipLaunchKernelGGL((k_score_logistic_mfma<DD>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w, (const float*)x, \
-                       ids, D, wt, sortkey, (const float*)c->blocks, (const int64_t*)c->block_off, logits)
+#define SP_LAUNCH_MF(DD)                                                                                          \
+    do {                                                                                                          \
+      if (logits)                                                                                                 \
+        hipLaunchKernelGGL((k_score_logistic_mfma<DD, true>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w,       \
+                           (const float*)x, ids, D, wt, sortkey, (const float*)c->blocks,                         \
+                           (const int64_t*)c->block_off, logits);                                                 \
+      else                                                                                                        \
+        hipLaunchKernelGGL((k_score_logistic_mfma<DD, false>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w,      \
+                           (const float*)x, ids, D, wt, sortkey, (const float*)c->blocks,                         \
+                           (const int64_t*)c->block_off, logits);                                                 \
+    } while (0)
     if (c->mfma_D == 64) SP_LAUNCH_MF(64);
     else if (c->mfma_D == 128) SP_LAUNCH_MF(128);
     else SP_LAUNCH_MF(256);

@@ -16,7 +16,8 @@
 //
 // Weights, table and bias of each (application, class tile) are packed once at
 // context creation into one contiguous block in exactly the order the lanes
-// read it from LDS, so staging is a straight copy (double-buffered).
+// read it from LDS, so staging is a straight global -> LDS DMA copy of the next
+// block while the current one is being used.
 #pragma once
 #include "sp_common.h"
 #include "sp_score_generic.h"
@@ -42,9 +43,9 @@ struct LogisticBlock {
   static constexpr int kW = D * 32;
   static constexpr int kTab = 16 * 64;
   static constexpr int kBias = 32;
-  static constexpr int kFloats = kW + kTab + kBias;
-  static constexpr int kVec4 = kFloats / 4;
-  static constexpr int kStage = (kVec4 + kMfThreads - 1) / kMfThreads;
+  static constexpr int kChunks = ((kW + kTab + kBias) / 4 + 63) / 64;   // 1 KB pieces, one LDS-DMA instruction each
+  static constexpr int kVec4 = kChunks * 64;
+  static constexpr int kFloats = kVec4 * 4;                             // padded to whole pieces
 };
 
 // Host-side packing of one application's head (called at context creation).
@@ -81,13 +82,88 @@ inline void pack_logistic_blocks(const float* W /*[d,C]*/, const float* b /*[C]*
   }
 }
 
+// Global -> LDS copy of one packed block with the LDS-DMA load (no registers in between): every lane
+// of a wavefront supplies the address of its own 16 bytes, the data lands at the (wave-uniform) LDS
+// base plus 16 * lane.  Wavefront w moves pieces w, w + 8, ...
 template <int D>
+__device__ __forceinline__ void stage_block(const float4* __restrict__ src, float4* dst_lds, int wave, int lane) {
+  using LB = LogisticBlock<D>;
+  for (int ch = wave; ch < LB::kChunks; ch += kMfWaves)
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + ch * 64 + lane),
+                                     (void __attribute__((address_space(3)))*)(dst_lds + ch * 64), 16, 0, 0);
+}
+
+// One class tile: logits from `cur`, online softmax update, exponentials x table; meanwhile the next
+// block streams into `nxt`.
+template <int D, bool DUMP>
+__device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const float4* __restrict__ next_src,
+                                           const float (&xr)[D / 2], f32x16& eacc, float& m2, int ct, int C, int g,
+                                           int r, int lane, int wave, bool valid, int64_t dump_row,
+                                           float* __restrict__ logits_out) {
+  using LB = LogisticBlock<D>;
+  if (next_src != nullptr) stage_block<D>(next_src, nxt, wave, lane);
+  // logits of this class tile, starting from the bias
+  f32x16 acc;
+  {
+    const float4* bp = cur + (LB::kW + LB::kTab) / 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 bq = bp[q * 2 + g];
+      acc[4 * q + 0] = bq.x; acc[4 * q + 1] = bq.y; acc[4 * q + 2] = bq.z; acc[4 * q + 3] = bq.w;
+    }
+  }
+  const float4* wp = cur + (g * (D / 8)) * 32 + r;
+#pragma unroll
+  for (int kk4 = 0; kk4 < D / 8; ++kk4) {
+    const float4 a4 = wp[kk4 * 32];
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, xr[4 * kk4 + 0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, xr[4 * kk4 + 1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, xr[4 * kk4 + 2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, xr[4 * kk4 + 3], acc, 0, 0, 0);
+  }
+  if (DUMP && valid) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int cls = 32 * ct + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (cls < C) logits_out[dump_row + cls] = acc[v];
+    }
+  }
+  // online softmax: the request's maximum spans both lane halves
+  float mt = acc[0];
+#pragma unroll
+  for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
+  mt = fmaxf(mt, __shfl_xor(mt, 32));
+  const float m2n = fmaxf(m2, mt * kLog2e);
+  const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
+  m2 = m2n;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    acc[v] = __builtin_amdgcn_exp2f(fmaf(acc[v], kLog2e, -m2n));
+    eacc[v] *= scale;
+  }
+  // exponentials x table tile (accuracies and the row of ones)
+  const float4* tp = cur + LB::kW / 4;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float4 t4 = tp[q * 64 + lane];
+    eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.x, acc[4 * q + 0], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.y, acc[4 * q + 1], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.z, acc[4 * q + 2], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.w, acc[4 * q + 3], eacc, 0, 0, 0);
+  }
+  __syncthreads();   // everyone is done with `cur`, and `nxt` has landed (the barrier waits for the DMA)
+}
+
+template <int D, bool DUMP>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_mfma(
     Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
     const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const float* __restrict__ blocks,
     const int64_t* __restrict__ block_off, float* __restrict__ logits_out) {
   using LB = LogisticBlock<D>;
-  extern __shared__ float4 lds4[];                       // two blocks
+  // two separate arrays (not one array split in two) so that the compiler can tell that the block
+  // being read and the block being filled never overlap
+  __shared__ float4 buf_a[LB::kVec4];
+  __shared__ float4 buf_b[LB::kVec4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int tile = blockIdx.x;
@@ -100,103 +176,45 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_mfma(
   const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];
   const int CT = (C + kClassTile - 1) / kClassTile;
 
+  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
+  stage_block<D>(src, buf_a, wave, lane);
+
   // this lane's half of its request's features: k = g*D/2 + [0, D/2)
   float xr[D / 2];
   {
     const float* row = x + (int64_t)id * d;
-    const bool vec_ok = (d & 3) == 0;
+    if ((d & 3) == 0) {                                  // rows are 16-byte aligned: whole float4 in or out of range
 #pragma unroll
-    for (int q = 0; q < D / 8; ++q) {
-      const int k0 = g * (D / 2) + 4 * q;
-      if (vec_ok && k0 + 3 < d) {
-        const float4 v = *reinterpret_cast<const float4*>(row + k0);
+      for (int q = 0; q < D / 8; ++q) {
+        const int k0 = g * (D / 2) + 4 * q;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 < d) v = *reinterpret_cast<const float4*>(row + k0);
         xr[4 * q + 0] = v.x; xr[4 * q + 1] = v.y; xr[4 * q + 2] = v.z; xr[4 * q + 3] = v.w;
-      } else {
+      }
+    } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xr[4 * q + j] = (k0 + j < d) ? row[k0 + j] : 0.f;
+      for (int q = 0; q < D / 2; ++q) {
+        const int k = g * (D / 2) + q;
+        xr[q] = (k < d) ? row[k] : 0.f;
       }
     }
   }
-
-  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
-  for (int i = tid; i < LB::kVec4; i += kMfThreads) lds4[i] = src[i];
   __syncthreads();
 
   float m2 = kNegBig;                                    // running maximum, in units of log2
   f32x16 eacc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
+  const int64_t dump_row = (int64_t)id * tb.Cmax;
 
-  for (int ct = 0; ct < CT; ++ct) {
-    const float4* cur = lds4 + (ct & 1) * LB::kVec4;
-    float4* nxt = lds4 + ((ct + 1) & 1) * LB::kVec4;
-    const bool more = ct + 1 < CT;
-    // prefetch the next block into registers (the last iteration re-reads its own block and drops it)
-    float4 stage[LB::kStage];
-    {
-      const float4* s2 = src + (size_t)(more ? ct + 1 : ct) * LB::kVec4;
-#pragma unroll
-      for (int i = 0; i < LB::kStage; ++i) stage[i] = s2[min(tid + i * kMfThreads, LB::kVec4 - 1)];
-    }
-    // logits of this class tile, starting from the bias
-    f32x16 acc;
-    {
-      const float4* bp = cur + (LB::kW + LB::kTab) / 4;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 bq = bp[q * 2 + g];
-        acc[4 * q + 0] = bq.x; acc[4 * q + 1] = bq.y; acc[4 * q + 2] = bq.z; acc[4 * q + 3] = bq.w;
-      }
-    }
-    const float4* wp = cur + (g * (D / 8)) * 32 + r;
-#pragma unroll
-    for (int kk4 = 0; kk4 < D / 8; ++kk4) {
-      const float4 a4 = wp[kk4 * 32];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, xr[4 * kk4 + 0], acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, xr[4 * kk4 + 1], acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, xr[4 * kk4 + 2], acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, xr[4 * kk4 + 3], acc, 0, 0, 0);
-    }
-    if (logits_out != nullptr && valid) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int cls = 32 * ct + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (cls < C) logits_out[(int64_t)id * tb.Cmax + cls] = acc[v];
-      }
-    }
-    // online softmax: the request's maximum spans both lane halves
-    float mt = acc[0];
-#pragma unroll
-    for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32));
-    const float m2n = fmaxf(m2, mt * kLog2e);
-    const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
-    m2 = m2n;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      acc[v] = __builtin_amdgcn_exp2f(fmaf(acc[v], kLog2e, -m2n));
-      eacc[v] *= scale;
-    }
-    // exponentials x table tile (accuracies and the row of ones)
-    const float4* tp = cur + LB::kW / 4;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 t4 = tp[q * 64 + lane];
-      eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.x, acc[4 * q + 0], eacc, 0, 0, 0);
-      eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.y, acc[4 * q + 1], eacc, 0, 0, 0);
-      eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.z, acc[4 * q + 2], eacc, 0, 0, 0);
-      eacc = __builtin_amdgcn_mfma_f32_32x32x2f32(t4.w, acc[4 * q + 3], eacc, 0, 0, 0);
-    }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < LB::kStage; ++i) {
-        const int idx = tid + i * kMfThreads;
-        if (idx < LB::kVec4) nxt[idx] = stage[i];
-      }
-    }
-    __syncthreads();
+  for (int ct = 0; ct < CT; ct += 2) {
+    class_tile<D, DUMP>(buf_a, buf_b, ct + 1 < CT ? src + (size_t)(ct + 1) * LB::kVec4 : nullptr, xr, eacc, m2, ct, C,
+                        g, r, lane, wave, valid, dump_row, logits_out);
+    if (ct + 1 < CT)
+      class_tile<D, DUMP>(buf_b, buf_a, ct + 2 < CT ? src + (size_t)(ct + 2) * LB::kVec4 : nullptr, xr, eacc, m2,
+                          ct + 1, C, g, r, lane, wave, valid, dump_row, logits_out);
   }
-  if (logits_out != nullptr) return;
+  if (DUMP) return;
 
   // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
   // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
