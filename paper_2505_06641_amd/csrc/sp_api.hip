@@ -13,7 +13,7 @@
 #include "sp_common.h"
 #include "sp_rounds.h"
 #include "sp_score_generic.h"
-#include "sp_score_mfma.h"
+#include "sp_score_split.h"
 #include "sp_sort.h"
 
 using namespace sp;
@@ -41,9 +41,9 @@ struct sp_ctx {
   bool done = false;
   size_t score_lds = 0;
   int mfma_D = 0;             // > 0: logistic heads run on the matrix-core kernel with this padded feature width
-  float* blocks = nullptr;    // packed (application, class tile) blocks for that kernel
-  int64_t* block_off = nullptr;
-  size_t mfma_lds = 0;
+  unsigned char* blocks = nullptr;   // packed (application, class tile) blocks for that kernel
+  int64_t* block_off = nullptr;      // [A] byte offsets
+  float* w_unscale = nullptr;        // [A] 2^-ew of each application's weight scaling
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -279,21 +279,22 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
 
 template <int D>
 sp_status pack_mfma_blocks_d(sp_ctx* c, const sp_profile* p) {
-  using LB = LogisticBlock<D>;
+  using SB = SplitBlock<D>;
   std::vector<int64_t> off(p->n_apps);
+  std::vector<float> unscale(p->n_apps);
   size_t total = 0;
   for (int a = 0; a < p->n_apps; ++a) {
     off[a] = (int64_t)total;
-    total += (size_t)((p->n_classes[a] + kClassTile - 1) / kClassTile) * LB::kFloats;
+    total += (size_t)((p->n_classes[a] + kClassTile - 1) / kClassTile) * SB::kBytes;
   }
-  std::vector<float> host(total);
+  std::vector<unsigned char> host(total);
   for (int a = 0; a < p->n_apps; ++a)
-    pack_logistic_blocks<D>((const float*)p->W1[a], p->b1[a], p->acc[a], p->feat_dim, p->n_classes[a],
-                            p->n_models[a], host.data() + off[a]);
+    unscale[a] = pack_split_blocks<D>((const float*)p->W1[a], p->b1[a], p->acc[a], p->feat_dim, p->n_classes[a],
+                                      p->n_models[a], host.data() + off[a]);
   sp_status s;
   if ((s = dev_upload(c, &c->blocks, host)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->block_off, off)) != SP_OK) return s;
-  c->mfma_lds = 0;   // the kernel's two block buffers are static LDS
+  if ((s = dev_upload(c, &c->w_unscale, unscale)) != SP_OK) return s;
   return SP_OK;
 }
 
@@ -327,13 +328,13 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
 #define SP_LAUNCH_MF(DD)                                                                                          \
     do {                                                                                                          \
       if (logits)                                                                                                 \
-        hipLaunchKernelGGL((k_score_logistic_mfma<DD, true>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w,       \
-                           (const float*)x, ids, D, wt, sortkey, (const float*)c->blocks,                         \
-                           (const int64_t*)c->block_off, logits);                                                 \
+        hipLaunchKernelGGL((k_score_logistic_split<DD, true>), dim3(grid), blk, 0, s, c->tb, c->w,                \
+                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
       else                                                                                                        \
-        hipLaunchKernelGGL((k_score_logistic_mfma<DD, false>), dim3(grid), blk, c->mfma_lds, s, c->tb, c->w,      \
-                           (const float*)x, ids, D, wt, sortkey, (const float*)c->blocks,                         \
-                           (const int64_t*)c->block_off, logits);                                                 \
+        hipLaunchKernelGGL((k_score_logistic_split<DD, false>), dim3(grid), blk, 0, s, c->tb, c->w,               \
+                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
     } while (0)
     if (c->mfma_D == 64) SP_LAUNCH_MF(64);
     else if (c->mfma_D == 128) SP_LAUNCH_MF(128);

@@ -1,0 +1,340 @@
+// Scoring kernel for logistic heads with float32 features on the matrix cores,
+// d <= 256, M <= 16: float32 products emulated by three half-precision MFMAs.
+//
+// Every float32 operand v is scaled by a power of two (per request row for the
+// features, per application for the weights; exact) into (-2^15, 2^15) and
+// split as v = hi + lo with hi = fp16(v), lo = fp16(v - hi): 22 significant
+// bits.  x.w is then  hi.hi + lo.hi + hi.lo  on v_mfma_f32_32x32x16_f16 with
+// float32 accumulation (fp16 x fp16 products are exact in float32; the dropped
+// lo.lo term is below 2^-22 of the product), at 16x the float32 MFMA rate per
+// instruction, i.e. 5.3x per float32 product.
+//
+// Work split as in the float32 kernel it replaces: one workgroup = 8 wavefronts
+// = 256 requests of one application; a wavefront keeps the split features of
+// its 32 requests in registers (D/2 VGPRs) and walks the classes 32 at a time.
+// Per class tile it computes the transposed logit tile Z^T[class, request]
+// (classes on the MFMA row axis: every lane owns one request column and 16 of
+// the 32 classes, so softmax statistics stay inside a lane), keeps a running
+// maximum per request (online softmax), splits the exponentials the same way
+// and feeds them back into the matrix cores against a [17 x 32] table tile
+// (the variants' per-class accuracies plus a row of ones): rows 0..15
+// accumulate sum_c exp(z_c) Acc[m][c], row 16 accumulates sum_c exp(z_c).  The
+// posterior is never formed or stored (Def. 4.1.2; Sec. 4.1 eq. (9)); EA =
+// rows 0..15 / row 16, then variance and key (Sec. 5.1.1 eq. (12)).
+//
+// Weights, table and bias of each (application, class tile) are packed once at
+// context creation into one contiguous block in exactly the order the lanes
+// read it from LDS; blocks stream global -> LDS by LDS-DMA into two buffers.
+#pragma once
+#include "sp_common.h"
+#include "sp_score_generic.h"
+
+namespace sp {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kMfWaves = 8;
+constexpr int kMfThreads = kMfWaves * kWave;
+constexpr int kMfTile = kMfWaves * 32;      // requests per workgroup
+constexpr int kClassTile = 32;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1e30f;
+constexpr int kSplitExp = 15;               // operands are scaled into (-2^15, 2^15)
+constexpr float kExpShift = 14.0f;          // exponentials are scaled into (0, 2^14]
+
+// Packed block of one (application, class tile), in 16-byte units (8 halves or 4 floats each):
+//   W     [D/16][2][64]  unit ((s*2 + part)*64 + lane): halves e = 0..7 hold part (0 = hi, 1 = lo) of
+//                        W'[k = (lane/32)*D/2 + 8 s + e][class = 32 ct + lane%32], W' = W * 2^ew
+//   table [2][2][64]     unit ((ks*2 + part)*64 + lane): halves e hold part of T[m = lane%32][class], class =
+//                        32 ct + 8 (2 ks + e/4) + 4 (lane/32) + e%4; T = Acc (m < M), 1 (m = 16), else 0
+//   bias  [4][2]         unit (q*2 + g): floats j = 0..3 hold b[32 ct + 8 q + 4 g + j], -1e30 beyond C
+template <int D>
+struct SplitBlock {
+  static constexpr int kWUnits = (D / 16) * 2 * 64;
+  static constexpr int kTabUnits = 2 * 2 * 64;
+  static constexpr int kBiasUnits = 8;
+  static constexpr int kChunks = (kWUnits + kTabUnits + kBiasUnits + 63) / 64;   // 1 KB pieces, one LDS-DMA each
+  static constexpr int kUnits = kChunks * 64;
+  static constexpr int kBytes = kUnits * 16;
+};
+
+inline uint16_t host_f32_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+
+inline void host_split(float v, uint16_t& hi, uint16_t& lo) {
+  const _Float16 h = (_Float16)v;
+  hi = __builtin_bit_cast(uint16_t, h);
+  lo = __builtin_bit_cast(uint16_t, (_Float16)(v - (float)h));
+}
+
+// Power-of-two scale that brings |v| <= vmax into (-2^15, 2^15): returns the exponent ew (scale = 2^ew).
+inline int host_scale_exponent(float vmax) {
+  if (!(vmax > 0.f) || !std::isfinite(vmax)) return 0;
+  int e = 0;
+  (void)std::frexp(vmax, &e);            // vmax = f * 2^e, f in [0.5, 1)
+  int ew = kSplitExp - e;
+  if (ew > 100) ew = 100;
+  if (ew < -100) ew = -100;
+  return ew;
+}
+
+// Host-side packing of one application's head (called at context creation).  Returns 2^-ew.
+template <int D>
+inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/, const float* acc /*[M,C]*/, int d,
+                               int C, int M, unsigned char* out /*[CT * kBytes]*/) {
+  using SB = SplitBlock<D>;
+  float wmax = 0.f;
+  for (size_t i = 0; i < (size_t)d * C; ++i) wmax = std::max(wmax, std::fabs(W[i]));
+  const int ew = host_scale_exponent(wmax);
+  const float ws = std::ldexp(1.0f, ew);
+  const int CT = (C + kClassTile - 1) / kClassTile;
+  for (int ct = 0; ct < CT; ++ct) {
+    unsigned char* blk = out + (size_t)ct * SB::kBytes;
+    std::memset(blk, 0, SB::kBytes);
+    uint16_t* wh = reinterpret_cast<uint16_t*>(blk);
+    for (int s = 0; s < D / 16; ++s)
+      for (int lane = 0; lane < 64; ++lane)
+        for (int e = 0; e < 8; ++e) {
+          const int k = (lane / 32) * (D / 2) + 8 * s + e, cls = 32 * ct + lane % 32;
+          const float v = (k < d && cls < C) ? W[(size_t)k * C + cls] * ws : 0.f;
+          uint16_t hi, lo;
+          host_split(v, hi, lo);
+          wh[((size_t)(s * 2 + 0) * 64 + lane) * 8 + e] = hi;
+          wh[((size_t)(s * 2 + 1) * 64 + lane) * 8 + e] = lo;
+        }
+    uint16_t* tab = wh + (size_t)SB::kWUnits * 8;
+    for (int ks = 0; ks < 2; ++ks)
+      for (int lane = 0; lane < 64; ++lane)
+        for (int e = 0; e < 8; ++e) {
+          const int m = lane % 32, cls = 32 * ct + 8 * (2 * ks + e / 4) + 4 * (lane / 32) + e % 4;
+          float v = 0.f;
+          if (cls < C) v = (m < M) ? acc[(size_t)m * C + cls] : (m == 16 ? 1.f : 0.f);
+          uint16_t hi, lo;
+          host_split(v, hi, lo);
+          tab[((size_t)(ks * 2 + 0) * 64 + lane) * 8 + e] = hi;
+          tab[((size_t)(ks * 2 + 1) * 64 + lane) * 8 + e] = lo;
+        }
+    float* bias = reinterpret_cast<float*>(blk + (size_t)(SB::kWUnits + SB::kTabUnits) * 16);
+    for (int q = 0; q < 4; ++q)
+      for (int g = 0; g < 2; ++g)
+        for (int j = 0; j < 4; ++j) {
+          const int cls = 32 * ct + 8 * q + 4 * g + j;
+          bias[(q * 2 + g) * 4 + j] = cls < C ? b[cls] : kNegBig;
+        }
+  }
+  return std::ldexp(1.0f, -ew);
+}
+
+// Global -> LDS copy of one packed block with the LDS-DMA load (no registers in between): every lane
+// of a wavefront supplies the address of its own 16 bytes, the data lands at the (wave-uniform) LDS
+// base plus 16 * lane.  Wavefront w moves pieces w, w + 8, ...
+template <int D>
+__device__ __forceinline__ void stage_block(const float4* __restrict__ src, float4* dst_lds, int wave, int lane) {
+  using SB = SplitBlock<D>;
+  for (int ch = wave; ch < SB::kChunks; ch += kMfWaves)
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + ch * 64 + lane),
+                                     (void __attribute__((address_space(3)))*)(dst_lds + ch * 64), 16, 0, 0);
+}
+
+__device__ __forceinline__ f16x8 as_f16x8(const float4& v) { return __builtin_bit_cast(f16x8, v); }
+
+// v = hi + lo in half precision (v already inside the fp16 range)
+__device__ __forceinline__ void split_f16(float v, _Float16& hi, _Float16& lo) {
+  hi = (_Float16)v;
+  lo = (_Float16)(v - (float)hi);
+}
+
+// One class tile: logits from `cur`, online softmax update, exponentials x table; meanwhile the next
+// block streams into `nxt`.
+template <int D, bool DUMP>
+__device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const float4* __restrict__ next_src,
+                                           const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale,
+                                           f32x16& eacc, float& m2, int ct, int C, int g, int lane, int wave,
+                                           bool valid, int64_t dump_row, float* __restrict__ logits_out) {
+  using SB = SplitBlock<D>;
+  if (next_src != nullptr) stage_block<D>(next_src, nxt, wave, lane);
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const float4* wp = cur + lane;
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    const f16x8 wh = as_f16x8(wp[(s * 2 + 0) * 64]);
+    const f16x8 wl = as_f16x8(wp[(s * 2 + 1) * 64]);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+  }
+  // z = acc * 2^-(ex + ew) + bias
+  {
+    const float4* bp = cur + SB::kWUnits + SB::kTabUnits;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 bq = bp[q * 2 + g];
+      acc[4 * q + 0] = fmaf(acc[4 * q + 0], unscale, bq.x);
+      acc[4 * q + 1] = fmaf(acc[4 * q + 1], unscale, bq.y);
+      acc[4 * q + 2] = fmaf(acc[4 * q + 2], unscale, bq.z);
+      acc[4 * q + 3] = fmaf(acc[4 * q + 3], unscale, bq.w);
+    }
+  }
+  if (DUMP && valid) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int cls = 32 * ct + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (cls < C) logits_out[dump_row + cls] = acc[v];
+    }
+  }
+  // online softmax: the request's maximum spans both lane halves
+  float mt = acc[0];
+#pragma unroll
+  for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
+  mt = fmaxf(mt, __shfl_xor(mt, 32));
+  const float m2n = fmaxf(m2, mt * kLog2e);
+  const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
+  m2 = m2n;
+  const float shift = kExpShift - m2n;
+  f16x8 ph[2], pl[2];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], kLog2e, shift));   // in (0, 2^14]
+    _Float16 hi, lo;
+    split_f16(p, hi, lo);
+    ph[v >> 3][v & 7] = hi;
+    pl[v >> 3][v & 7] = lo;
+    eacc[v] *= scale;
+  }
+  // exponentials x table tile (accuracies and the row of ones)
+  const float4* tp = cur + SB::kWUnits + lane;
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const f16x8 th = as_f16x8(tp[(ks * 2 + 0) * 64]);
+    const f16x8 tl = as_f16x8(tp[(ks * 2 + 1) * 64]);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, ph[ks], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, ph[ks], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, pl[ks], eacc, 0, 0, 0);
+  }
+  __syncthreads();   // everyone is done with `cur`, and `nxt` has landed (the barrier waits for the DMA)
+}
+
+template <int D, bool DUMP>
+__global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
+    Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
+    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
+    const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
+    float* __restrict__ logits_out) {
+  using SB = SplitBlock<D>;
+  // two separate arrays (not one array split in two) so that the compiler can tell that the block
+  // being read and the block being filled never overlap
+  __shared__ float4 buf_a[SB::kUnits];
+  __shared__ float4 buf_b[SB::kUnits];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int tile = blockIdx.x;
+  if (tile >= w.tile_start[tb.A]) return;
+  const int a = find_segment(w.tile_start, tb.A, tile);
+  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
+  const int pos = seg_b + (tile - w.tile_start[a]) * kMfTile + wave * 32 + r;
+  const bool valid = pos < seg_e;
+  const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
+  const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];
+  const int CT = (C + kClassTile - 1) / kClassTile;
+
+  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
+  stage_block<D>(src, buf_a, wave, lane);
+
+  // this lane's half of its request's features, k = g*D/2 + [0, D/2): scale the row into (-2^15, 2^15), split
+  f16x8 xh[D / 16], xl[D / 16];
+  float unscale;
+  {
+    float xr[D / 2];
+    const float* row = x + (int64_t)id * d;
+    if ((d & 3) == 0) {                                  // rows are 16-byte aligned: whole float4 in or out of range
+#pragma unroll
+      for (int q = 0; q < D / 8; ++q) {
+        const int k0 = g * (D / 2) + 4 * q;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 < d) v = *reinterpret_cast<const float4*>(row + k0);
+        xr[4 * q + 0] = v.x; xr[4 * q + 1] = v.y; xr[4 * q + 2] = v.z; xr[4 * q + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < D / 2; ++q) {
+        const int k = g * (D / 2) + q;
+        xr[q] = (k < d) ? row[k] : 0.f;
+      }
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int q = 0; q < D / 2; ++q) amax = fmaxf(amax, fabsf(xr[q]));
+    amax = fmaxf(amax, __shfl_xor(amax, 32));
+    // amax = f * 2^e with f in [0.5, 1): scale by 2^(15 - e); rows of zeros (or denormals) keep scale 1
+    int ex = 0;
+    if (amax >= 1e-30f && amax <= 3e38f) ex = kSplitExp - (int)(((__float_as_uint(amax) >> 23) & 0xffu) - 126u);
+    const float xs = __uint_as_float((uint32_t)(127 + ex) << 23);
+    unscale = __uint_as_float((uint32_t)(127 - ex) << 23) * w_unscale[a];
+#pragma unroll
+    for (int q = 0; q < D / 2; ++q) {
+      _Float16 hi, lo;
+      split_f16(xr[q] * xs, hi, lo);
+      xh[q >> 3][q & 7] = hi;
+      xl[q >> 3][q & 7] = lo;
+    }
+  }
+  __syncthreads();
+
+  float m2 = kNegBig;                                    // running maximum, in units of log2
+  f32x16 eacc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
+  const int64_t dump_row = (int64_t)id * tb.Cmax;
+
+  for (int ct = 0; ct < CT; ct += 2) {
+    class_tile<D, DUMP>(buf_a, buf_b, ct + 1 < CT ? src + (size_t)(ct + 1) * SB::kUnits : nullptr, xh, xl, unscale,
+                        eacc, m2, ct, C, g, lane, wave, valid, dump_row, logits_out);
+    if (ct + 1 < CT)
+      class_tile<D, DUMP>(buf_b, buf_a, ct + 2 < CT ? src + (size_t)(ct + 2) * SB::kUnits : nullptr, xh, xl, unscale,
+                          eacc, m2, ct + 1, C, g, lane, wave, valid, dump_row, logits_out);
+  }
+  if (DUMP) return;
+
+  // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
+  // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
+  const float ssum = __shfl(eacc[8], r);
+  const float inv = 1.0f / ssum;
+  float ea[8];
+  float part = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    ea[v] = (m < M) ? eacc[v] * inv : 0.f;
+    part += ea[v];
+  }
+  const float mean = (part + __shfl_xor(part, 32)) / (float)M;
+  float vpart = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    const float dv = ea[v] - mean;
+    vpart += (m < M) ? dv * dv : 0.f;
+  }
+  const float var = (vpart + __shfl_xor(vpart, 32)) / (float)M;
+  if (!valid) return;
+  float* rowo = w.ea + (int64_t)id * tb.Mmax;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    if (m < tb.Mmax) rowo[m] = ea[v];
+  }
+  if (g == 0) {
+    const float Di = Dl[id], wi = wt[id];
+    uint32_t err = 0;
+    if (!(Di > 0.f)) err |= kErrDeadline;
+    if (!(wi >= 0.f)) err |= kErrWeight;
+    if (err) atomicOr(&w.st->err, err);
+    const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
+    w.key[id] = key;
+    sortkey[pos] = ~__float_as_uint(key);
+  }
+}
+
+}  // namespace sp
