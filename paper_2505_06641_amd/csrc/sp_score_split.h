@@ -156,14 +156,29 @@ __device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  // weight fragments are fetched kPre k-steps ahead of the MFMAs that use them
+  constexpr int S = D / 16;
+  constexpr int kPre = S < 3 ? S : 3;
   const float4* wp = cur + lane;
+  float4 wbuf[kPre][2];
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    const f16x8 wh = as_f16x8(wp[(s * 2 + 0) * 64]);
-    const f16x8 wl = as_f16x8(wp[(s * 2 + 1) * 64]);
+  for (int s = 0; s < kPre; ++s) {
+    wbuf[s][0] = wp[(s * 2 + 0) * 64];
+    wbuf[s][1] = wp[(s * 2 + 1) * 64];
+  }
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const f16x8 wh = as_f16x8(wbuf[s % kPre][0]);
+    const f16x8 wl = as_f16x8(wbuf[s % kPre][1]);
+    if (s + kPre < S) {
+      wbuf[s % kPre][0] = wp[((s + kPre) * 2 + 0) * 64];
+      wbuf[s % kPre][1] = wp[((s + kPre) * 2 + 1) * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep the reads of step s + kPre ahead of the MFMAs of step s
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
   // z = acc * 2^-(ex + ew) + bias
   {
