@@ -186,7 +186,8 @@ sp_status sp_debug_dump(sp_ctx* ctx, int32_t kind, void* stream, const void* x_d
                         const int32_t* app_dev, void* dst_dev);
 
 /* Benchmark aid.  sp_set_timing(ctx, 1) makes sp_score and sp_schedule record
- * HIP events around their stages (and after each of the first 4096 rounds);
+ * HIP events around their stages; sp_set_timing(ctx, 2) additionally records
+ * one after each of the first 4096 rounds (this slows the rounds down a little);
  * sp_get_timing / sp_get_round_times wait for those events and return the
  * elapsed device times (per-round times in milliseconds, HOST array of
  * `capacity` floats, *n_out = number written).  SP_ESTATE if timing is off or

@@ -233,8 +233,9 @@ class Context:
         n_log = min(sm.n_rounds, log_capacity)
         return rc, sm.as_dict(), [log[i].as_dict() for i in range(n_log)]
 
-    def sp_set_timing(self, enable=True):
-        return self._check(self.lib.sp_set_timing(self.h, 1 if enable else 0), "sp_set_timing")
+    def sp_set_timing(self, level=1):
+        """0 off, 1 stage events, 2 stage events and one event per round."""
+        return self._check(self.lib.sp_set_timing(self.h, int(level)), "sp_set_timing")
 
     def sp_get_timing(self):
         t = sp_timing()

@@ -47,6 +47,7 @@ struct sp_ctx {
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
+  bool timing_rounds = false;
   bool timed_score = false, timed_rounds = false;
   hipEvent_t ev[6] = {};                 // group start, score start, score stop, order stop, rounds start, rounds stop
   std::vector<hipEvent_t> round_ev;      // one after each timed round
@@ -525,7 +526,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
     if (chunk <= 0) break;
     for (int i = 0; i < chunk; ++i) {
       launch_round(c, s, nullptr, nullptr);
-      if (tm && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
+      if (tm && c->timing_rounds && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
     }
     if (tm) SP_HIP(c, hipEventRecord(c->ev[5], s));
     st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
@@ -607,6 +608,7 @@ sp_status sp_set_timing(sp_ctx* c, int32_t enable) {
     for (hipEvent_t& e : c->round_ev) SP_HIP(c, hipEventCreate(&e));
   }
   c->timing = enable != 0;
+  c->timing_rounds = enable >= 2;
   c->timed_score = c->timed_rounds = false;
   return SP_OK;
 }
