@@ -240,10 +240,10 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &w.unit_start, A + 1)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.ea, N * Mmax)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.key, N)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &w.D_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.D_s, N + 16)) != SP_OK) return s;      // +16: the window scan reads whole 16-groups
   if ((s = dev_alloc(c, &w.w_s, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.key_s, N)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &w.alive_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.alive_s, N + 16)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.head, 2 * (size_t)A)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.model, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.round_of, N)) != SP_OK) return s;

@@ -20,6 +20,7 @@
 namespace sp {
 
 constexpr int kRoundThreads = 256;
+constexpr int kScanSpan = 16 * kRoundThreads;   // positions looked at per scan step
 
 __device__ __forceinline__ unsigned long long pack_candidate(float score, uint32_t cand_id) {
   return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - cand_id);
@@ -62,21 +63,50 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   const int head = w.head[(r & 1) * tb.A + a];
 
   // ---- candidate window: first B live requests in service order ----
+  // Each step looks at kScanSpan consecutive positions, 16 per thread (one 16-byte load of pending flags,
+  // four of deadlines), so that even an application whose queue is almost entirely dead is walked in
+  // a handful of dependent memory round trips.
   int found = 0;
-  for (int base = head; base < seg_e && found < B; base += kRoundThreads) {
-    const int pos = base + tid;
-    bool live = false;
-    if (pos < seg_e) live = w.alive_s[pos] != 0 && !is_dead(kind, w.D_s[pos], E0);
-    const unsigned long long vote = __ballot(live);
-    if (lane == 0) wave_cnt[wave] = __popcll(vote);
+  for (int base = head & ~15; base < seg_e && found < B; base += kScanSpan) {
+    const int p0 = base + 16 * tid;
+    uint32_t mask = 0;
+    if (p0 < seg_e) {                                  // D_s and alive_s are padded by 16 entries: always whole vectors
+      const uint4 al = *reinterpret_cast<const uint4*>(w.alive_s + p0);
+      const uint32_t alw[4] = {al.x, al.y, al.z, al.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 dv = *reinterpret_cast<const float4*>(w.D_s + p0 + 4 * q);
+        const float dd[4] = {dv.x, dv.y, dv.z, dv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int pos = p0 + 4 * q + j;
+          const bool live = ((alw[q] >> (8 * j)) & 0xffu) != 0 && !is_dead(kind, dd[j], E0) && pos >= head && pos < seg_e;
+          mask |= live ? (1u << (4 * q + j)) : 0u;
+        }
+      }
+    }
+    // exclusive prefix of the per-thread counts over the workgroup
+    const int cnt = __popc(mask);
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_cnt[wave] = incl;
     __syncthreads();
     int before = found, total = found;
     for (int i = 0; i < kRoundThreads / 64; ++i) {
       if (i < wave) before += wave_cnt[i];
       total += wave_cnt[i];
     }
-    const int rank = before + __popcll(vote & ((lane == 0) ? 0ull : (~0ull >> (64 - lane))));
-    if (live && rank < B) win[rank] = pos;
+    int rank = before + incl - cnt;
+    uint32_t mk = mask;
+    while (mk != 0 && rank < B) {
+      const int j = __ffs((int)mk) - 1;
+      mk &= mk - 1;
+      win[rank++] = p0 + j;
+    }
     found = total;
     __syncthreads();
   }
