@@ -19,8 +19,8 @@
 
 namespace sp {
 
-constexpr int kRoundThreads = 256;
-constexpr int kScanSpan = 16 * kRoundThreads;   // positions looked at per scan step
+constexpr int kRoundThreads = 512;
+constexpr int kPairLanes = 8;                       // lanes that share one pair of batch sizes in the triangle
 
 __device__ __forceinline__ unsigned long long pack_candidate(float score, uint32_t cand_id) {
   return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - cand_id);
@@ -63,24 +63,25 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   const int head = w.head[(r & 1) * tb.A + a];
 
   // ---- candidate window: first B live requests in service order ----
-  // Each step looks at kScanSpan consecutive positions, 16 per thread (one 16-byte load of pending flags,
-  // four of deadlines), so that even an application whose queue is almost entirely dead is walked in
-  // a handful of dependent memory round trips.
+  // The first step looks at 4 positions per thread (1024 per workgroup, enough while most of the queue
+  // is live), later steps at 16 per thread, so that even an application whose queue is almost entirely
+  // dead is walked in a handful of dependent memory round trips.  D_s and alive_s are padded by 16
+  // entries, so whole vectors can always be loaded.
   int found = 0;
-  for (int base = head & ~15; base < seg_e && found < B; base += kScanSpan) {
-    const int p0 = base + 16 * tid;
+  int base = head & ~3;
+  for (int step = 0; base < seg_e && found < B; ++step) {
+    const int nq = step == 0 ? 1 : 4;                  // groups of 4 positions per thread
+    const int p0 = base + 4 * nq * tid;
     uint32_t mask = 0;
-    if (p0 < seg_e) {                                  // D_s and alive_s are padded by 16 entries: always whole vectors
-      const uint4 al = *reinterpret_cast<const uint4*>(w.alive_s + p0);
-      const uint32_t alw[4] = {al.x, al.y, al.z, al.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
+    if (p0 < seg_e) {
+      for (int q = 0; q < nq; ++q) {
+        const uint32_t alw = *reinterpret_cast<const uint32_t*>(w.alive_s + p0 + 4 * q);
         const float4 dv = *reinterpret_cast<const float4*>(w.D_s + p0 + 4 * q);
         const float dd[4] = {dv.x, dv.y, dv.z, dv.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int pos = p0 + 4 * q + j;
-          const bool live = ((alw[q] >> (8 * j)) & 0xffu) != 0 && !is_dead(kind, dd[j], E0) && pos >= head && pos < seg_e;
+          const bool live = ((alw >> (8 * j)) & 0xffu) != 0 && !is_dead(kind, dd[j], E0) && pos >= head && pos < seg_e;
           mask |= live ? (1u << (4 * q + j)) : 0u;
         }
       }
@@ -108,6 +109,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
       win[rank++] = p0 + j;
     }
     found = total;
+    base += 4 * nq * kRoundThreads;
     __syncthreads();
   }
   const int nb = min(found, B);
@@ -131,27 +133,49 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   }
   __syncthreads();
 
-  // ---- triangle: groups of 4 lanes own the batch sizes (p+1, B-p) ----
+  // ---- triangle: groups of kPairLanes lanes own the batch sizes (p+1, B-p) ----
+  // Both batch sizes of a pair run in the same loop (two independent chains per lane), the completion
+  // time of each batch size is carried as a float pair so that the loop stays in float32.
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
-  const int sub = tid & 3, grp = tid >> 2;
+  const int sub = tid % kPairLanes, grp = tid / kPairLanes;
   const int n_pairs = (B + 1) / 2;
   unsigned long long best = 0ull;
-  for (int p = grp; p < n_pairs; p += kRoundThreads / 4) {
-    for (int side = 0; side < 2; ++side) {
-      const int b = side == 0 ? p + 1 : B - p;
-      if (side == 1 && b == p + 1) break;          // middle batch size of an odd B
-      float s = 0.f;
-      if (b <= nb) {
-        const double E = t + (double)lat[b - 1];
-        for (int j = sub; j < b; j += 4) s += aj[j] * one_minus_penalty(kind, Dj[j], invDj[j], E);
-      }
-      s += __shfl_xor(s, 1);
-      s += __shfl_xor(s, 2);
-      if (b <= nb && sub == 0) {
-        const uint32_t cid = (uint32_t)((a * tb.Mmax + m) * B + (b - 1));
-        const unsigned long long pk = pack_candidate(s, cid);
+  for (int p = grp; p < n_pairs; p += kRoundThreads / kPairLanes) {
+    const int b1 = p + 1, b2 = B - p;                 // b1 <= b2; equal for the middle size of an odd B
+    const double E1 = t + (double)lat[b1 - 1], E2 = t + (double)lat[b2 - 1];
+    const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
+    const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
+    const int n1 = b1 <= nb ? b1 : 0, n2 = (b2 <= nb && b2 != b1) ? b2 : 0;
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int j = sub;
+    for (; j < n1 && j < n2; j += kPairLanes) {                 // both batch sizes use request j
+      const float av = aj[j], dv = Dj[j], iv = invDj[j];
+      s1 += av * one_minus_penalty_f32(kind, dv, iv, e1h, e1l);
+      s2 += av * one_minus_penalty_f32(kind, dv, iv, e2h, e2l);
+    }
+    for (; j < n1; j += kPairLanes) s1 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e1h, e1l);
+    for (; j + kPairLanes < n2; j += 2 * kPairLanes) {                       // only the larger one: two requests per trip
+      s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
+      s3 += aj[j + kPairLanes] * one_minus_penalty_f32(kind, Dj[j + kPairLanes], invDj[j + kPairLanes], e2h, e2l);
+    }
+    if (j < n2) s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
+    s2 += s3;
+#pragma unroll
+    for (int o = 1; o < kPairLanes; o <<= 1) {
+      s1 += __shfl_xor(s1, o);
+      s2 += __shfl_xor(s2, o);
+    }
+    if (sub == 0) {
+      const uint32_t cid0 = (uint32_t)((a * tb.Mmax + m) * B);
+      if (n1 > 0) {
+        const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
         best = pk > best ? pk : best;
-        if (cube_out) cube_out[cid] = s;
+        if (cube_out) cube_out[cid0 + b1 - 1] = s1;
+      }
+      if (n2 > 0) {
+        const unsigned long long pk = pack_candidate(s2, cid0 + (uint32_t)(b2 - 1));
+        best = pk > best ? pk : best;
+        if (cube_out) cube_out[cid0 + b2 - 1] = s2;
       }
     }
   }
