@@ -26,6 +26,7 @@ METRIC = "request x model x batch candidates scored/s"
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_MFMA_F16_TFLOPS = 2500.0
 PEAK_VALU_F32_TFLOPS = 157.3
 
 
@@ -129,21 +130,28 @@ def main():
     tflops = flops / (k_avg * 1e-3) / 1e12
     gbs = k_bytes / (k_avg * 1e-3) / 1e9
     ai = flops / k_bytes
+    split = p.feat_dtype == wl.F32 and int(p.hidden_dim) == 0 and int(p.feat_dim) <= 256
     if p.feat_dtype == wl.BF16:
-        peak_c, ridge = PEAK_MFMA_BF16_TFLOPS, PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+        peak_c, peak_note = PEAK_MFMA_BF16_TFLOPS, "bf16 dense MFMA peak"
+    elif split:
+        # the kernel forms every float32 product from three fp16 MFMAs (hi.hi + lo.hi + hi.lo), so its
+        # ceiling for float32 flops is a third of the fp16 MFMA peak
+        peak_c, peak_note = PEAK_MFMA_F16_TFLOPS / 3.0, "fp16 dense MFMA peak / 3 (three fp16 MFMAs per float32 product)"
     else:
-        peak_c, ridge = PEAK_MFMA_F32_TFLOPS, PEAK_MFMA_F32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+        peak_c, peak_note = PEAK_VALU_F32_TFLOPS, "float32 vector peak (generic kernel)"
+    ridge = peak_c * 1e12 / (PEAK_HBM_GBS * 1e9)
     if ai >= ridge:
-        roof = {"bound": "mfma", "achieved": tflops, "peak": peak_c, "unit": "TFLOP/s", "frac": tflops / peak_c}
+        roof = {"bound": "mfma" if (split or p.feat_dtype == wl.BF16) else "alu", "achieved": tflops, "peak": peak_c, "unit": "TFLOP/s", "frac": tflops / peak_c}
     else:
         roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
     roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": None,
+                 "peak_note": peak_note, "x_fp32_mfma_peak": tflops / PEAK_MFMA_F32_TFLOPS,
                  "algorithmic_flops": flops, "algorithmic_bytes": k_bytes, "hbm_gbs": gbs, "tflops": tflops})
 
     out = {
         "metric": METRIC, "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16" if p.feat_dtype == wl.BF16 else "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16" if p.feat_dtype == wl.BF16 else ("f32 (fp16 hi/lo split MFMA, f32 accumulate)" if split else "f32"), "data": "synthetic",
         "config": {"workload": f"{w.name}: {A} applications, C={int(np.max(p.n_classes))}, M={m_max}, B={B}, "
                                f"N={n}, d={int(p.feat_dim)}, H={int(p.hidden_dim)}, seed {w.seed}; "
                                f"one scoring pass + {'greedy rounds until exhausted' if rounds <= 0 else str(rounds) + ' greedy rounds'}",

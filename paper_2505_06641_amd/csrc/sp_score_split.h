@@ -24,7 +24,7 @@
 //
 // Weights, table and bias of each (application, class tile) are packed once at
 // context creation into one contiguous block in exactly the order the lanes
-// read it from LDS; blocks stream global -> LDS by LDS-DMA into two buffers.
+// read it from LDS; blocks stream global -> LDS by LDS-DMA, three buffers deep.
 #pragma once
 #include "sp_common.h"
 #include "sp_score_generic.h"
@@ -144,22 +144,21 @@ __device__ __forceinline__ void split_f16(float v, _Float16& hi, _Float16& lo) {
   lo = (_Float16)(v - (float)hi);
 }
 
-// One class tile: logits from `cur`, online softmax update, exponentials x table; meanwhile the next
-// block streams into `nxt`.
-template <int D, bool DUMP>
-__device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const float4* __restrict__ next_src,
-                                           const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale,
-                                           f32x16& eacc, float& m2, int ct, int C, int g, int lane, int wave,
-                                           bool valid, int64_t dump_row, float* __restrict__ logits_out) {
-  using SB = SplitBlock<D>;
-  if (next_src != nullptr) stage_block<D>(next_src, nxt, wave, lane);
-  f32x16 acc;
+// Matrix phase of one class tile: acc = (W' x') for the tile's 32 classes and the wavefront's 32 requests.
+template <int D>
+__device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16],
+                                             f32x16& acc, int lane) {
+  // two accumulators (even and odd k-steps) so that consecutive MFMAs do not wait for each other's result
+  f32x16 acc2;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int v = 0; v < 16; ++v) {
+    acc[v] = 0.f;
+    acc2[v] = 0.f;
+  }
   // weight fragments are fetched kPre k-steps ahead of the MFMAs that use them
   constexpr int S = D / 16;
   constexpr int kPre = S < 3 ? S : 3;
-  const float4* wp = cur + lane;
+  const float4* wp = blk + lane;
   float4 wbuf[kPre][2];
 #pragma unroll
   for (int s = 0; s < kPre; ++s) {
@@ -176,13 +175,26 @@ __device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const
     }
     __builtin_amdgcn_sched_barrier(0);   // keep the reads of step s + kPre ahead of the MFMAs of step s
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+    acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc2, 0, 0, 0);
+    if (s & 1)
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc2, 0, 0, 0);
+    else
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
-  // z = acc * 2^-(ex + ew) + bias
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
+}
+
+// Softmax phase of one class tile (mostly vector ALU work): logits = acc * 2^-(ex+ew) + bias, online
+// softmax update, exponentials x table tile.
+template <int D, bool DUMP>
+__device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, float unscale, f32x16& eacc, float& m2,
+                                              int ct, int C, int g, int lane, bool valid, int64_t dump_row,
+                                              float* __restrict__ logits_out) {
+  using SB = SplitBlock<D>;
   {
-    const float4* bp = cur + SB::kWUnits + SB::kTabUnits;
+    const float4* bp = blk + SB::kWUnits + SB::kTabUnits;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const float4 bq = bp[q * 2 + g];
@@ -199,7 +211,7 @@ __device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const
       if (cls < C) logits_out[dump_row + cls] = acc[v];
     }
   }
-  // online softmax: the request's maximum spans both lane halves
+  // the request's maximum spans both lane halves
   float mt = acc[0];
 #pragma unroll
   for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
@@ -219,7 +231,7 @@ __device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const
     eacc[v] *= scale;
   }
   // exponentials x table tile (accuracies and the row of ones)
-  const float4* tp = cur + SB::kWUnits + lane;
+  const float4* tp = blk + SB::kWUnits + lane;
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const f16x8 th = as_f16x8(tp[(ks * 2 + 0) * 64]);
@@ -228,7 +240,6 @@ __device__ __forceinline__ void class_tile(const float4* cur, float4* nxt, const
     eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, ph[ks], eacc, 0, 0, 0);
     eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, pl[ks], eacc, 0, 0, 0);
   }
-  __syncthreads();   // everyone is done with `cur`, and `nxt` has landed (the barrier waits for the DMA)
 }
 
 template <int D, bool DUMP>
@@ -238,10 +249,11 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
     float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
-  // two separate arrays (not one array split in two) so that the compiler can tell that the block
-  // being read and the block being filled never overlap
+  // three separate arrays (not one array split in three) so that the compiler can tell that the
+  // blocks being read and the block being filled never overlap
   __shared__ float4 buf_a[SB::kUnits];
   __shared__ float4 buf_b[SB::kUnits];
+  __shared__ float4 buf_c[SB::kUnits];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int tile = blockIdx.x;
@@ -263,7 +275,31 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   {
     float xr[D / 2];
     const float* row = x + (int64_t)id * d;
-    if ((d & 3) == 0) {                                  // rows are 16-byte aligned: whole float4 in or out of range
+    if (D == 256 && (d & 3) == 0) {
+      // Coalesced: the wavefront reads whole rows (one 16-byte piece per lane, 1 KB per instruction),
+      // parks eight rows at a time in the block buffers that are still idle, and every lane then
+      // picks its own half row out of LDS.  Row stride 66 and half offset 33 (in 16-byte units) keep
+      // both the writes and the reads free of bank conflicts.
+      float4* scratch = (wave < kMfWaves / 2 ? buf_b : buf_c) + (wave % (kMfWaves / 2)) * (8 * 66);
+#pragma unroll 1
+      for (int ps = 0; ps < 4; ++ps) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int rid = __shfl(id, 8 * ps + i);
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (4 * lane < d) v = *reinterpret_cast<const float4*>(x + (int64_t)rid * d + 4 * lane);
+          scratch[i * 66 + g * 33 + r] = v;
+        }
+        if ((r >> 3) == ps) {
+          const float4* mine = scratch + (r & 7) * 66 + g * 33;
+#pragma unroll
+          for (int q = 0; q < D / 8; ++q) {
+            const float4 v = mine[q];
+            xr[4 * q + 0] = v.x; xr[4 * q + 1] = v.y; xr[4 * q + 2] = v.z; xr[4 * q + 3] = v.w;
+          }
+        }
+      }
+    } else if ((d & 3) == 0) {                           // rows are 16-byte aligned: whole float4 in or out of range
 #pragma unroll
       for (int q = 0; q < D / 8; ++q) {
         const int k0 = g * (D / 2) + 4 * q;
@@ -303,12 +339,38 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
   const int64_t dump_row = (int64_t)id * tb.Cmax;
 
-  for (int ct = 0; ct < CT; ct += 2) {
-    class_tile<D, DUMP>(buf_a, buf_b, ct + 1 < CT ? src + (size_t)(ct + 1) * SB::kUnits : nullptr, xh, xl, unscale,
-                        eacc, m2, ct, C, g, lane, wave, valid, dump_row, logits_out);
-    if (ct + 1 < CT)
-      class_tile<D, DUMP>(buf_b, buf_a, ct + 2 < CT ? src + (size_t)(ct + 2) * SB::kUnits : nullptr, xh, xl, unscale,
-                          eacc, m2, ct + 1, C, g, lane, wave, valid, dump_row, logits_out);
+  // The two wavefronts that share a SIMD run half a tile apart: wavefronts 0..3 do the matrix phase of
+  // tile t while wavefronts 4..7 do the softmax phase of tile t-1, then they swap, so the matrix cores
+  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 starts streaming into the
+  // third buffer at the beginning of tile t and must have landed two phases later.
+  const bool late = wave >= kMfWaves / 2;
+  f32x16 acc;
+#define SP_TILE(T, CUR, NXT, PRV)                                                                              \
+  if ((T) < CT) {                                                                                              \
+    if ((T) + 1 < CT) stage_block<D>(src + (size_t)((T) + 1) * SB::kUnits, NXT, wave, lane);                    \
+    if (!late) {                                                                                               \
+      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
+    } else if ((T) > 0) {                                                                                      \
+      softmax_phase<D, DUMP>(PRV, acc, unscale, eacc, m2, (T) - 1, C, g, lane, valid, dump_row, logits_out);   \
+    }                                                                                                          \
+    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing is handed over through LDS here */      \
+    if (!late) {                                                                                               \
+      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+    } else {                                                                                                   \
+      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
+    }                                                                                                          \
+    __syncthreads();                       /* block T+1 has landed (the barrier waits for the DMA) */          \
+  }
+  for (int t0 = 0; t0 < CT; t0 += 3) {
+    SP_TILE(t0, buf_a, buf_b, buf_c)
+    SP_TILE(t0 + 1, buf_b, buf_c, buf_a)
+    SP_TILE(t0 + 2, buf_c, buf_a, buf_b)
+  }
+#undef SP_TILE
+  if (late) {
+    const int last = (CT - 1) % 3;
+    const float4* lb = last == 0 ? buf_a : (last == 1 ? buf_b : buf_c);
+    softmax_phase<D, DUMP>(lb, acc, unscale, eacc, m2, CT - 1, C, g, lane, valid, dump_row, logits_out);
   }
   if (DUMP) return;
 
