@@ -24,7 +24,8 @@
 //
 // Weights, table and bias of each (application, class tile) are packed once at
 // context creation into one contiguous block in exactly the order the lanes
-// read it from LDS; blocks stream global -> LDS by LDS-DMA, three buffers deep.
+// read it from LDS; the next block is fetched through registers while the current one is in use
+// (three LDS buffers).
 #pragma once
 #include "sp_common.h"
 #include "sp_score_generic.h"
@@ -32,6 +33,7 @@
 namespace sp {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kMfWaves = 8;
@@ -127,13 +129,53 @@ inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/,
 
 // Global -> LDS copy of one packed block with the LDS-DMA load (no registers in between): every lane
 // of a wavefront supplies the address of its own 16 bytes, the data lands at the (wave-uniform) LDS
-// base plus 16 * lane.  Wavefront w moves pieces w, w + 8, ...
+// base plus 16 * lane.  Used for the first block only: the instruction keeps the issuing wavefront
+// busy for about 300 cycles per KB on this part, too slow for the steady state.
 template <int D>
-__device__ __forceinline__ void stage_block(const float4* __restrict__ src, float4* dst_lds, int wave, int lane) {
+__device__ __forceinline__ void stage_block_dma(const float4* __restrict__ src, float4* dst_lds, int wave, int lane) {
   using SB = SplitBlock<D>;
   for (int ch = wave; ch < SB::kChunks; ch += kMfWaves)
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + ch * 64 + lane),
                                      (void __attribute__((address_space(3)))*)(dst_lds + ch * 64), 16, 0, 0);
+}
+
+// Steady-state staging through registers, half a block per phase: the loads are issued when a phase
+// starts (fetch), the data is parked in LDS when it ends (park), so the L2 latency hides behind the
+// phase's own work.  Part 0 covers the first (up to) three units per thread, part 1 the rest.
+template <int D>
+struct StageRegs {
+  static constexpr int kPerThread = (SplitBlock<D>::kUnits + kMfThreads - 1) / kMfThreads;   // 16-byte units
+  static constexpr int kCount0 = kPerThread < 3 ? kPerThread : 3;
+  static constexpr int kCount1 = kPerThread - kCount0;
+  static_assert(kCount1 <= 3, "block too large for the two-part staging");
+  f32x4 v[3];
+};
+// The loads are written as inline assembly so that the compiler cannot sink them down to their use
+// (it would, across the whole phase); since it then does not know that they are asynchronous, the
+// matching s_waitcnt is explicit in stage_park, tied to the same registers.
+template <int D, int PART>
+__device__ __forceinline__ void stage_fetch(const float4* __restrict__ src, StageRegs<D>& st, int tid) {
+  using SB = SplitBlock<D>;
+  constexpr int kFirst = PART == 0 ? 0 : StageRegs<D>::kCount0 * kMfThreads;
+  constexpr int kCount = PART == 0 ? StageRegs<D>::kCount0 : StageRegs<D>::kCount1;
+#pragma unroll
+  for (int i = 0; i < kCount; ++i) {
+    const float4* p = src + min(kFirst + tid + i * kMfThreads, SB::kUnits - 1);
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(st.v[i]) : "v"(p) : "memory");
+  }
+}
+template <int D, int PART>
+__device__ __forceinline__ void stage_park(float4* dst_lds, StageRegs<D>& st, int tid) {
+  using SB = SplitBlock<D>;
+  constexpr int kFirst = PART == 0 ? 0 : StageRegs<D>::kCount0 * kMfThreads;
+  constexpr int kCount = PART == 0 ? StageRegs<D>::kCount0 : StageRegs<D>::kCount1;
+  if (kCount == 0) return;
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(st.v[0]), "+v"(st.v[1]), "+v"(st.v[2]) : : "memory");
+#pragma unroll
+  for (int i = 0; i < kCount; ++i) {
+    const int idx = kFirst + tid + i * kMfThreads;
+    if (idx < SB::kUnits) reinterpret_cast<f32x4*>(dst_lds)[idx] = st.v[i];
+  }
 }
 
 __device__ __forceinline__ f16x8 as_f16x8(const float4& v) { return __builtin_bit_cast(f16x8, v); }
@@ -148,16 +190,11 @@ __device__ __forceinline__ void split_f16(float v, _Float16& hi, _Float16& lo) {
 template <int D>
 __device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16],
                                              f32x16& acc, int lane) {
-  // two accumulators (even and odd k-steps) so that consecutive MFMAs do not wait for each other's result
-  f32x16 acc2;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    acc[v] = 0.f;
-    acc2[v] = 0.f;
-  }
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   // weight fragments are fetched kPre k-steps ahead of the MFMAs that use them
   constexpr int S = D / 16;
-  constexpr int kPre = S < 3 ? S : 3;
+  constexpr int kPre = S < 2 ? S : 2;
   const float4* wp = blk + lane;
   float4 wbuf[kPre][2];
 #pragma unroll
@@ -175,15 +212,17 @@ __device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh
     }
     __builtin_amdgcn_sched_barrier(0);   // keep the reads of step s + kPre ahead of the MFMAs of step s
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
-    acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc2, 0, 0, 0);
-    if (s & 1)
-      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc2, 0, 0, 0);
-    else
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
+}
+
+__device__ __forceinline__ float other_half(float v, int g) {
+  // value held by lane ^ 32 (v_permlane32_swap: pure vector ALU, does not go through the LDS queue)
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(g == 0 ? sw[1] : sw[0]);
 }
 
 // Softmax phase of one class tile (mostly vector ALU work): logits = acc * 2^-(ex+ew) + bias, online
@@ -193,16 +232,18 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
                                               int ct, int C, int g, int lane, bool valid, int64_t dump_row,
                                               float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
+  float4 bq[4];
   {
     const float4* bp = blk + SB::kWUnits + SB::kTabUnits;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 bq = bp[q * 2 + g];
-      acc[4 * q + 0] = fmaf(acc[4 * q + 0], unscale, bq.x);
-      acc[4 * q + 1] = fmaf(acc[4 * q + 1], unscale, bq.y);
-      acc[4 * q + 2] = fmaf(acc[4 * q + 2], unscale, bq.z);
-      acc[4 * q + 3] = fmaf(acc[4 * q + 3], unscale, bq.w);
-    }
+    for (int q = 0; q < 4; ++q) bq[q] = bp[q * 2 + g];
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    acc[4 * q + 0] = fmaf(acc[4 * q + 0], unscale, bq[q].x);
+    acc[4 * q + 1] = fmaf(acc[4 * q + 1], unscale, bq[q].y);
+    acc[4 * q + 2] = fmaf(acc[4 * q + 2], unscale, bq[q].z);
+    acc[4 * q + 3] = fmaf(acc[4 * q + 3], unscale, bq[q].w);
   }
   if (DUMP && valid) {
 #pragma unroll
@@ -215,7 +256,7 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   float mt = acc[0];
 #pragma unroll
   for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
-  mt = fmaxf(mt, __shfl_xor(mt, 32));
+  mt = fmaxf(mt, other_half(mt, g));
   const float m2n = fmaxf(m2, mt * kLog2e);
   const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
   m2 = m2n;
@@ -267,7 +308,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   const int CT = (C + kClassTile - 1) / kClassTile;
 
   const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
-  stage_block<D>(src, buf_a, wave, lane);
+  stage_block_dma<D>(src, buf_a, wave, lane);
 
   // this lane's half of its request's features, k = g*D/2 + [0, D/2): scale the row into (-2^15, 2^15), split
   f16x8 xh[D / 16], xl[D / 16];
@@ -341,26 +382,33 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
 
   // The two wavefronts that share a SIMD run half a tile apart: wavefronts 0..3 do the matrix phase of
   // tile t while wavefronts 4..7 do the softmax phase of tile t-1, then they swap, so the matrix cores
-  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 starts streaming into the
-  // third buffer at the beginning of tile t and must have landed two phases later.
+  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 is fetched into the third
+  // buffer in two halves, one per phase.
   const bool late = wave >= kMfWaves / 2;
   f32x16 acc;
 #define SP_TILE(T, CUR, NXT, PRV)                                                                              \
   if ((T) < CT) {                                                                                              \
-    if ((T) + 1 < CT) stage_block<D>(src + (size_t)((T) + 1) * SB::kUnits, NXT, wave, lane);                    \
+    const bool more = (T) + 1 < CT;                                                                            \
+    const float4* nsrc = src + (size_t)(more ? (T) + 1 : (T)) * SB::kUnits;                                    \
+    stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
     if (!late) {                                                                                               \
       logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
     } else if ((T) > 0) {                                                                                      \
       softmax_phase<D, DUMP>(PRV, acc, unscale, eacc, m2, (T) - 1, C, g, lane, valid, dump_row, logits_out);   \
     }                                                                                                          \
-    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing is handed over through LDS here */      \
+    stage_park<D, 0>(NXT, stg, tid);      /* (after the last tile: a copy nobody reads) */                     \
+    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing read in the next phase was written here */ \
+    stage_fetch<D, 1>(nsrc, stg, tid);                                                                         \
     if (!late) {                                                                                               \
       softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
     } else {                                                                                                   \
       logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
     }                                                                                                          \
-    __syncthreads();                       /* block T+1 has landed (the barrier waits for the DMA) */          \
+    stage_park<D, 1>(NXT, stg, tid);                                                                           \
+    __syncthreads();                       /* block T+1 is complete in LDS */                                  \
   }
+  StageRegs<D> stg;
+  stg.v[0] = stg.v[1] = stg.v[2] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int t0 = 0; t0 < CT; t0 += 3) {
     SP_TILE(t0, buf_a, buf_b, buf_c)
     SP_TILE(t0 + 1, buf_b, buf_c, buf_a)
