@@ -190,8 +190,14 @@ __device__ __forceinline__ void split_f16(float v, _Float16& hi, _Float16& lo) {
 template <int D>
 __device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16],
                                              f32x16& acc, int lane) {
+  // two accumulator chains: a dependent 32x32x16 MFMA can only issue every ~52 cycles, an independent
+  // one every 32
+  f32x16 acc2;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int v = 0; v < 16; ++v) {
+    acc[v] = 0.f;
+    acc2[v] = 0.f;
+  }
   // weight fragments are fetched kPre k-steps ahead of the MFMAs that use them
   constexpr int S = D / 16;
   constexpr int kPre = S < 2 ? S : 2;
@@ -212,10 +218,15 @@ __device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh
     }
     __builtin_amdgcn_sched_barrier(0);   // keep the reads of step s + kPre ahead of the MFMAs of step s
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+    acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc2, 0, 0, 0);
+    if (s & 1)
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc2, 0, 0, 0);
+    else
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
 }
 
 __device__ __forceinline__ float other_half(float v, int g) {
@@ -322,15 +333,23 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       // picks its own half row out of LDS.  Row stride 66 and half offset 33 (in 16-byte units) keep
       // both the writes and the reads free of bank conflicts.
       float4* scratch = (wave < kMfWaves / 2 ? buf_b : buf_c) + (wave % (kMfWaves / 2)) * (8 * 66);
-#pragma unroll 1
-      for (int ps = 0; ps < 4; ++ps) {
+      // rows of pass ps+1 are already in flight while pass ps goes through LDS
+      float4 rows[2][8];
+      auto fetch_rows = [&](int ps, float4 (&dst)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int rid = __shfl(id, 8 * ps + i);
-          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (4 * lane < d) v = *reinterpret_cast<const float4*>(x + (int64_t)rid * d + 4 * lane);
-          scratch[i * 66 + g * 33 + r] = v;
+          dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (4 * lane < d) dst[i] = *reinterpret_cast<const float4*>(x + (int64_t)rid * d + 4 * lane);
         }
+      };
+      fetch_rows(0, rows[0]);
+#pragma unroll
+      for (int ps = 0; ps < 4; ++ps) {
+        if (ps + 1 < 4) fetch_rows(ps + 1, rows[(ps + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) scratch[i * 66 + g * 33 + r] = rows[ps & 1][i];
         if ((r >> 3) == ps) {
           const float4* mine = scratch + (r & 7) * 66 + g * 33;
 #pragma unroll
@@ -339,6 +358,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
             xr[4 * q + 0] = v.x; xr[4 * q + 1] = v.y; xr[4 * q + 2] = v.z; xr[4 * q + 3] = v.w;
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else if ((d & 3) == 0) {                           // rows are 16-byte aligned: whole float4 in or out of range
 #pragma unroll
