@@ -29,7 +29,8 @@ struct sp_ctx {
   int A = 0, d = 0, H = 0, B = 0, Mmax = 0, Cmax = 0, dtype = 0;
   int64_t cap = 0;
   uint32_t* bufK[2] = {nullptr, nullptr};
-  int32_t* bufV[2] = {nullptr, nullptr};
+  int32_t* bufV[3] = {nullptr, nullptr, nullptr};
+  uint32_t* scan_tot = nullptr;  // [max(A,1)+1, 256] column totals / bases of the radix scan
   uint32_t* hist = nullptr;
   int64_t hist_units = 0;
   int32_t* seg1 = nullptr;    // [2] single-segment plan for the application pass
@@ -102,9 +103,9 @@ sp_status dev_upload(sp_ctx* c, T** out, const std::vector<T>& host) {
 }
 
 int unit_size_for(int64_t n) {
-  int64_t s = ((n / 512 + 63) / 64) * 64;
+  int64_t s = ((n / 2048 + 63) / 64) * 64;
   if (s < 256) s = 256;
-  if (s > 4096) s = 4096;
+  if (s > 1024) s = 1024;
   return (int)s;
 }
 
@@ -256,11 +257,15 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &w.log, (size_t)w.log_cap)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.last_ids, B)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.st, 1)) != SP_OK) return s;
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 2; ++i)
     if ((s = dev_alloc(c, &c->bufK[i], N)) != SP_OK) return s;
+  for (int i = 0; i < 3; ++i)
     if ((s = dev_alloc(c, &c->bufV[i], N)) != SP_OK) return s;
-  }
-  c->hist_units = (int64_t)std::max<size_t>(512, N / 256) + A + 8;
+  if ((s = dev_alloc(c, &w.id_s, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.D_g, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.w_g, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->scan_tot, (size_t)(A + 1) * 256)) != SP_OK) return s;
+  c->hist_units = (int64_t)std::max<size_t>(2048, N / 256) + A + 8;
   if ((s = dev_alloc(c, &c->hist, (size_t)c->hist_units * 256)) != SP_OK) return s;
   if ((s = dev_alloc(c, &c->seg1, 2)) != SP_OK) return s;
   if ((s = dev_alloc(c, &c->unit1, 2)) != SP_OK) return s;
@@ -355,9 +360,10 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, c
                 const int32_t* vals, int shift, uint32_t* keys_out, int32_t* vals_out) {
   const int blocks = (max_units + kSortWaves - 1) / kSortWaves;
   hipLaunchKernelGGL(k_radix_hist, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, shift, c->hist);
-  hipLaunchKernelGGL(k_radix_scan, dim3(plan.nseg), dim3(256), 0, s, plan, c->hist);
+  hipLaunchKernelGGL(k_radix_scan_cols, dim3(plan.nseg * 16), dim3(256), 0, s, plan, c->hist, c->scan_tot);
+  hipLaunchKernelGGL(k_radix_scan_base, dim3(plan.nseg), dim3(256), 0, s, plan, c->scan_tot);
   hipLaunchKernelGGL(k_radix_scatter, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, vals, shift,
-                     (const uint32_t*)c->hist, keys_out, vals_out);
+                     (const uint32_t*)c->hist, (const uint32_t*)c->scan_tot, keys_out, vals_out);
 }
 
 void launch_round(sp_ctx* c, hipStream_t s, int32_t* ids_out, float* cube) {
@@ -460,22 +466,21 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     if (tm) SP_HIP(c, hipEventRecord(c->ev[1], s));
     launch_score(c, s, x_dev, curV, deadline_ms_dev, weight_dev, sortkey, nullptr);
     if (tm) SP_HIP(c, hipEventRecord(c->ev[2], s));
-    // service order: inside each application by (key descending, id ascending)
-    const int32_t* ids_all = curV;
+    // service order: inside each application by (key descending, id ascending).  The passes carry
+    // positions of the grouped array (identity to start with), the grouped ids stay where they are.
     SortPlan per_app{w.seg, w.unit_start, A, unit};
     const int units2 = (n + unit - 1) / unit + A;
     uint32_t *k_in = sortkey, *k_out = curK;
-    int32_t *v_in = curV, *v_out = altV;
+    const int32_t* v_in = nullptr;
+    int32_t *v_out = altV, *v_spare = c->bufV[2];
     for (int p = 0; p < 4; ++p) {
       radix_pass(c, s, per_app, units2, k_in, v_in, 8 * p, k_out, v_out);
       std::swap(k_in, k_out);
-      std::swap(v_in, v_out);
+      v_in = v_out;
+      std::swap(v_out, v_spare);
     }
-    // four passes: the result is back in the buffer the application pass wrote,
-    // whose tail (requests with an invalid application) was never touched
-    w.id_s = v_in;
-    hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg,
-                       (const int32_t*)v_in, ids_all, deadline_ms_dev, weight_dev, w);
+    hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
+                       (const uint32_t*)k_in, (const int32_t*)curV, w);
     if (tm) {
       SP_HIP(c, hipEventRecord(c->ev[3], s));
       c->timed_score = true;

@@ -64,6 +64,8 @@ struct Window {
   int32_t* unit_start;        // [A+1] prefix of sort units
   float* ea;                  // [n, Mmax]
   float* key;                 // [n]
+  float* D_g;                 // [n] deadline at each position of the application-grouped (pre-order) array
+  float* w_g;                 // [n] weight, same indexing
   int32_t* id_s;              // [n] request id at each service position
   float* D_s;                 // [n]
   float* w_s;                 // [n]

@@ -61,6 +61,8 @@ __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w
   float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
   w.key[id] = key;
   sortkey[pos] = ~__float_as_uint(key);
+  w.D_g[pos] = Di;
+  w.w_g[pos] = wi;
   float* row = w.ea + (int64_t)id * tb.Mmax;
   for (int m = 0; m < tb.Mmax; ++m) {
     float v = 0.f;

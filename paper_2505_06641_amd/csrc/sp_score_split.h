@@ -479,6 +479,8 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
     w.key[id] = key;
     sortkey[pos] = ~__float_as_uint(key);
+    w.D_g[pos] = Di;
+    w.w_g[pos] = wi;
   }
 }
 

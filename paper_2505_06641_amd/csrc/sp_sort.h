@@ -89,42 +89,63 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, c
   }
 }
 
-// One workgroup of 256 threads per segment; thread = digit.  Turns the
-// per-unit counts into destination offsets: order (digit, unit), base seg[s].
-__global__ __launch_bounds__(256) void k_radix_scan(SortPlan sp, uint32_t* __restrict__ hist) {
-  __shared__ uint32_t tot[256];
-  const int s = blockIdx.x, dgt = threadIdx.x;
+// Destination offsets from the per-unit counts, in two small kernels.
+// k_radix_scan_cols: workgroup (segment s, digit group dg) turns the 16 columns hist[.][16 dg .. 16 dg + 15]
+// of the segment's units into exclusive prefixes down the column (16 threads per column, each walking
+// every 16th unit) and stores the column totals.  k_radix_scan_base: one workgroup per segment scans the
+// 256 totals and adds the segment start.  Offset of (unit u, digit d) = base[s][d] + hist[u][d].
+constexpr int kScanColThreads = 16;
+
+__global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* __restrict__ hist,
+                                                         uint32_t* __restrict__ tot /*[nseg,256]*/) {
+  const int s = blockIdx.x / 16, dg = blockIdx.x % 16;
+  const int col = threadIdx.x / kScanColThreads, j = threadIdx.x % kScanColThreads;
+  const int dgt = dg * 16 + col;
   const int u0 = sp.unit_start[s], u1 = sp.unit_start[s + 1];
-  uint32_t sum = 0;
-  for (int u = u0; u < u1; ++u) sum += hist[(int64_t)u * 256 + dgt];
-  tot[dgt] = sum;
+  uint32_t carry = 0;                                    // total of the column over the chunks done so far
+  for (int ub = u0; ub < u1; ub += kScanColThreads) {
+    const int u = ub + j;
+    const uint32_t c = u < u1 ? hist[(int64_t)u * 256 + dgt] : 0u;
+    uint32_t incl = c;
+#pragma unroll
+    for (int o = 1; o < kScanColThreads; o <<= 1) {
+      const uint32_t up = __shfl_up(incl, o, kScanColThreads);
+      if (j >= o) incl += up;
+    }
+    if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c;
+    carry += __shfl(incl, kScanColThreads - 1, kScanColThreads);
+  }
+  if (j == 0) tot[(int64_t)s * 256 + dgt] = carry;
+}
+
+__global__ __launch_bounds__(256) void k_radix_scan_base(SortPlan sp, uint32_t* __restrict__ tot) {
+  __shared__ uint32_t sc[256];
+  const int s = blockIdx.x, dgt = threadIdx.x;
+  const uint32_t mine = tot[(int64_t)s * 256 + dgt];
+  sc[dgt] = mine;
   __syncthreads();
-  // exclusive scan over the 256 digit totals (Hillis-Steele in LDS)
-  for (int o = 1; o < 256; o <<= 1) {
-    const uint32_t v = (dgt >= o) ? tot[dgt - o] : 0u;
+  for (int o = 1; o < 256; o <<= 1) {                    // Hillis-Steele inclusive scan in LDS
+    const uint32_t v = (dgt >= o) ? sc[dgt - o] : 0u;
     __syncthreads();
-    tot[dgt] += v;
+    sc[dgt] += v;
     __syncthreads();
   }
-  uint32_t run = (uint32_t)sp.seg[s] + tot[dgt] - sum;
-  for (int u = u0; u < u1; ++u) {
-    const uint32_t c = hist[(int64_t)u * 256 + dgt];
-    hist[(int64_t)u * 256 + dgt] = run;
-    run += c;
-  }
+  tot[(int64_t)s * 256 + dgt] = (uint32_t)sp.seg[s] + sc[dgt] - mine;
 }
 
 // vals_in == nullptr means the identity (value = element index).
 __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
     SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift,
-    const uint32_t* __restrict__ offs, uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
+    const uint32_t* __restrict__ offs, const uint32_t* __restrict__ base, uint32_t* __restrict__ keys_out,
+    int32_t* __restrict__ vals_out) {
   __shared__ uint32_t run[kSortWaves][256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.x * kSortWaves + wave;
   int beg = 0, end = 0;
   const bool have = unit_range(sp, u, beg, end);
   if (!have) return;   // no block-wide barrier below: wavefronts are independent
-  for (int i = lane; i < 256; i += 64) run[wave][i] = offs[(int64_t)u * 256 + i];
+  const int sg = find_segment(sp.unit_start, sp.nseg, u);
+  for (int i = lane; i < 256; i += 64) run[wave][i] = offs[(int64_t)u * 256 + i] + base[(int64_t)sg * 256 + i];
   wave_sync();
   const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int base = beg; base < end; base += 64) {
@@ -181,28 +202,30 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
   }
 }
 
-// After the last pass: per service position the request id, deadline, weight
-// and key; and the per-request outputs reset to "not served".
+// After the last pass.  The passes carried positions of the application-grouped array as values and the
+// inverted key bits as keys, so per service position: id, deadline and weight are gathers from the
+// grouped arrays (local to the application's range), the key comes straight from the sorted key bits.
 __global__ void k_finish_order(int n, int n_valid_at /*index into seg*/, const int32_t* __restrict__ seg,
-                               const int32_t* __restrict__ ids_valid, const int32_t* __restrict__ ids_all,
-                               const float* __restrict__ D, const float* __restrict__ wt, Window w) {
+                               const int32_t* __restrict__ grouped_pos, const uint32_t* __restrict__ sorted_keys,
+                               const int32_t* __restrict__ ids_grouped, Window w) {
   const int pos = blockIdx.x * blockDim.x + threadIdx.x;
   if (pos >= n) return;
   const int nv = seg[n_valid_at];
-  const int id = pos < nv ? ids_valid[pos] : ids_all[pos];
   if (pos < nv) {
-    w.id_s[pos] = id;
-    w.D_s[pos] = D[id];
-    w.w_s[pos] = wt[id];
-    w.key_s[pos] = w.key[id];
+    const int gp = grouped_pos[pos];
+    w.id_s[pos] = ids_grouped[gp];
+    w.D_s[pos] = w.D_g[gp];
+    w.w_s[pos] = w.w_g[gp];
+    w.key_s[pos] = __uint_as_float(~sorted_keys[pos]);
     w.alive_s[pos] = 1;
   } else {
     w.alive_s[pos] = 0;
   }
-  w.model[id] = -1;
-  w.round_of[id] = -1;
-  w.order_of[id] = 0;
-  w.util[id] = 0.f;
+  // per-request outputs back to "not served" (indexed by request id: every id in [0, n) once)
+  w.model[pos] = -1;
+  w.round_of[pos] = -1;
+  w.order_of[pos] = 0;
+  w.util[pos] = 0.f;
 }
 
 }  // namespace sp
