@@ -14,6 +14,7 @@
 #include "sp_rounds.h"
 #include "sp_score_generic.h"
 #include "sp_score_split.h"
+#include "sp_score_mlp.h"
 #include "sp_sort.h"
 
 using namespace sp;
@@ -45,6 +46,9 @@ struct sp_ctx {
   unsigned char* blocks = nullptr;   // packed (application, class tile) blocks for that kernel
   int64_t* block_off = nullptr;      // [A] byte offsets
   float* w_unscale = nullptr;        // [A] 2^-ew of each application's weight scaling
+  bool mlp_bf16 = false;             // bf16 MLP heads run on the matrix-core MLP kernel
+  unsigned char* w1p = nullptr;      // packed layer-1 slices for that kernel
+  int64_t* w1_off = nullptr;         // [A] byte offsets
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -183,6 +187,7 @@ sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
 }
 
 sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p);
+sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p);
 
 sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   const int A = p->n_apps, B = p->max_batch;
@@ -231,6 +236,9 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if (c->H == 0 && c->dtype == SP_F32 && c->d <= 256) {
     c->mfma_D = c->d <= 64 ? 64 : (c->d <= 128 ? 128 : 256);
     if ((s = pack_mfma_blocks(c, p)) != SP_OK) return s;
+  } else if (c->H > 0 && c->H <= kMlpH && c->dtype == SP_BF16 && (c->d % 8) == 0) {
+    c->mlp_bf16 = true;
+    if ((s = pack_mlp_blocks(c, p)) != SP_OK) return s;
   }
 
   // window buffers
@@ -295,11 +303,48 @@ sp_status pack_mfma_blocks_d(sp_ctx* c, const sp_profile* p) {
   }
   std::vector<unsigned char> host(total);
   for (int a = 0; a < p->n_apps; ++a)
-    unscale[a] = pack_split_blocks<D>((const float*)p->W1[a], p->b1[a], p->acc[a], p->feat_dim, p->n_classes[a],
+    unscale[a] = pack_split_blocks<D, kMapRows>((const float*)p->W1[a], p->b1[a], p->acc[a], p->feat_dim, p->n_classes[a],
                                       p->n_models[a], host.data() + off[a]);
   sp_status s;
   if ((s = dev_upload(c, &c->blocks, host)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->block_off, off)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->w_unscale, unscale)) != SP_OK) return s;
+  return SP_OK;
+}
+
+// bf16 MLP heads: layer-1 slices as they are, layer 2 + table + bias as split blocks over the hidden units
+sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p) {
+  using SB = SplitBlock<kMlpH>;
+  const int A = p->n_apps, d = p->feat_dim, H = p->hidden_dim;
+  const int nkc = (d + kL1Chunk - 1) / kL1Chunk;
+  std::vector<int64_t> off1(A), off2(A);
+  std::vector<float> unscale(A);
+  size_t tot2 = 0;
+  for (int a = 0; a < A; ++a) {
+    off1[a] = (int64_t)((size_t)a * mlp_layer1_bytes(d));
+    off2[a] = (int64_t)tot2;
+    tot2 += (size_t)((p->n_classes[a] + kClassTile - 1) / kClassTile) * SB::kBytes;
+  }
+  std::vector<unsigned char> h1((size_t)A * mlp_layer1_bytes(d), 0), h2(tot2);
+  std::vector<float> w2f;
+  for (int a = 0; a < A; ++a) {
+    pack_mlp_layer1((const uint16_t*)p->W1[a], d, H, reinterpret_cast<uint16_t*>(h1.data() + off1[a]));
+    std::memcpy(h1.data() + off1[a] + (size_t)nkc * kL1Units * 16, p->b1[a], (size_t)H * sizeof(float));
+    const int C = p->n_classes[a];
+    const uint16_t* w2 = (const uint16_t*)p->W2[a];
+    w2f.resize((size_t)H * C);
+    for (size_t i = 0; i < w2f.size(); ++i) {
+      const uint32_t bits = (uint32_t)w2[i] << 16;
+      std::memcpy(&w2f[i], &bits, 4);
+    }
+    unscale[a] = pack_split_blocks<kMlpH, kMapTile>(w2f.data(), p->b2[a], p->acc[a], H, C, p->n_models[a],
+                                                    h2.data() + off2[a]);
+  }
+  sp_status s;
+  if ((s = dev_upload(c, &c->w1p, h1)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->w1_off, off1)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->blocks, h2)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->block_off, off2)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->w_unscale, unscale)) != SP_OK) return s;
   return SP_OK;
 }
@@ -324,10 +369,24 @@ void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, con
     hipLaunchKernelGGL((k_score_generic<T, 16>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
 }
 
-int score_tile(const sp_ctx* c) { return c->mfma_D > 0 ? kMfTile : kScoreTile; }
+int score_tile(const sp_ctx* c) { return (c->mfma_D > 0 || c->mlp_bf16) ? kMfTile : kScoreTile; }
 
 void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
                   uint32_t* sortkey, float* logits) {
+  if (c->mlp_bf16) {
+    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
+    if (logits)
+      hipLaunchKernelGGL((k_score_mlp_bf16<true>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w, (const uint16_t*)x,
+                         ids, D, wt, sortkey, (const unsigned char*)c->w1p, (const int64_t*)c->w1_off,
+                         (const unsigned char*)c->blocks, (const int64_t*)c->block_off, (const float*)c->w_unscale,
+                         logits);
+    else
+      hipLaunchKernelGGL((k_score_mlp_bf16<false>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w, (const uint16_t*)x,
+                         ids, D, wt, sortkey, (const unsigned char*)c->w1p, (const int64_t*)c->w1_off,
+                         (const unsigned char*)c->blocks, (const int64_t*)c->block_off, (const float*)c->w_unscale,
+                         logits);
+    return;
+  }
   if (c->mfma_D > 0) {
     const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
     const dim3 blk(kMfThreads);

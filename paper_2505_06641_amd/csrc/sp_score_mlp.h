@@ -1,0 +1,188 @@
+// Scoring kernel for one-hidden-layer ReLU heads with bfloat16 features and weights (H <= 256, M <= 16).
+//
+// Layer 1, h = relu(x W1 + b1), runs on v_mfma_f32_32x32x16_bf16 (bf16 x bf16 products are exact,
+// float32 accumulation): a wavefront owns 32 requests and keeps the whole transposed hidden tile
+// H^T[hidden, request] in eight float32 accumulators (128 VGPRs) while it streams its requests' features
+// 64 input channels at a time; the matching W1 slices (32 KB each, packed at context creation in the
+// order the lanes read them) go through two LDS buffers shared by the workgroup's eight wavefronts.
+// The hidden tile never leaves the registers: after bias and ReLU each request's row is scaled by a
+// power of two, split into half-precision hi + lo (22 bits) and used directly as the input operand of
+// the class tiles (layer 2 + online softmax + accuracy-table contraction) shared with the logistic
+// kernel, whose weight blocks are packed with the row order an MFMA output tile has (Def. 4.1.2;
+// Sec. 4.1 eq. (9); Sec. 5.1.1 eq. (12)).
+#pragma once
+#include "sp_common.h"
+#include "sp_score_split.h"
+
+namespace sp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kMlpH = 256;                       // padded hidden width (zero weights beyond H)
+constexpr int kL1Chunk = 64;                     // input channels per W1 slice
+constexpr int kL1Units = (kMlpH / 32) * (kL1Chunk / 16) * 64;   // 16-byte units per slice (2048 = 32 KB)
+constexpr int kL1PerThread = kL1Units / kMfThreads;             // 4
+
+// Bytes of one application's packed layer 1: its slices, then the bias padded with zeros to kMlpH floats.
+inline size_t mlp_layer1_bytes(int d) { return (size_t)((d + kL1Chunk - 1) / kL1Chunk) * kL1Units * 16 + kMlpH * sizeof(float); }
+
+// W1 slice kc of an application, 16-byte units:
+//   unit ((hb*4 + s)*64 + lane), element e: W1[k = 64 kc + 16 s + 8 (lane/32) + e][hidden = 32 hb + lane%32]
+inline void pack_mlp_layer1(const uint16_t* W1 /*[d,H] bf16 bits*/, int d, int H, uint16_t* out /*[nkc * kL1Units * 8]*/) {
+  const int nkc = (d + kL1Chunk - 1) / kL1Chunk;
+  for (int kc = 0; kc < nkc; ++kc)
+    for (int hb = 0; hb < kMlpH / 32; ++hb)
+      for (int s = 0; s < kL1Chunk / 16; ++s)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int e = 0; e < 8; ++e) {
+            const int k = kL1Chunk * kc + 16 * s + 8 * (lane / 32) + e, hid = 32 * hb + lane % 32;
+            out[(((size_t)kc * kL1Units) + ((hb * 4 + s) * 64 + lane)) * 8 + e] =
+                (k < d && hid < H) ? W1[(size_t)k * H + hid] : (uint16_t)0;
+          }
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const f32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <bool DUMP>
+__global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
+    Tables tb, Window w, const uint16_t* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
+    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ w1p,
+    const int64_t* __restrict__ w1_off /*[A] bytes*/, const unsigned char* __restrict__ blocks,
+    const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
+    float* __restrict__ logits_out) {
+  constexpr int D = kMlpH;
+  using SB = SplitBlock<D>;
+  __shared__ float4 buf_a[SB::kUnits];
+  __shared__ float4 buf_b[SB::kUnits];
+  __shared__ float4 buf_c[SB::kUnits];
+  static_assert(kL1Units <= SB::kUnits, "a W1 slice must fit in one block buffer");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int tile = blockIdx.x;
+  if (tile >= w.tile_start[tb.A]) return;
+  const int a = find_segment(w.tile_start, tb.A, tile);
+  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
+  const int pos = seg_b + (tile - w.tile_start[a]) * kMfTile + wave * 32 + r;
+  const bool valid = pos < seg_e;
+  const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
+  const int d = tb.d, H = tb.H, C = tb.n_classes[a], M = tb.n_models[a];
+  const int CT = (C + kClassTile - 1) / kClassTile;
+  const int nkc = (d + kL1Chunk - 1) / kL1Chunk;
+
+  // the first class-tile block can travel while layer 1 runs
+  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
+  stage_block_dma<D>(src, buf_a, wave, lane);
+
+  // ---- layer 1 ----
+  const f32x4* w1 = reinterpret_cast<const f32x4*>(w1p + w1_off[a]);
+  const uint16_t* row = x + (int64_t)id * d + 8 * g;     // this lane half's 8 channels of every 16
+  f32x16 hacc[kMlpH / 32];
+#pragma unroll
+  for (int hb = 0; hb < kMlpH / 32; ++hb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) hacc[hb][v] = 0.f;
+
+  // slice 0 and the first feature pieces, the plain way
+  f32x4 xs[kL1Chunk / 16];
+  {
+    f32x4* dst = reinterpret_cast<f32x4*>(buf_b);
+#pragma unroll
+    for (int i = 0; i < kL1PerThread; ++i) dst[tid + i * kMfThreads] = w1[tid + i * kMfThreads];
+#pragma unroll
+    for (int s = 0; s < kL1Chunk / 16; ++s) {
+      xs[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (16 * s + 8 * g < d) xs[s] = *reinterpret_cast<const f32x4*>(row + 16 * s);
+    }
+  }
+  __syncthreads();
+  f32x4 wst[kL1PerThread], xn[kL1Chunk / 16];
+#pragma unroll
+  for (int i = 0; i < kL1PerThread; ++i) wst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < kL1Chunk / 16; ++s) xn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int kc = 0; kc < nkc; ++kc) {
+    const f32x4* cur = reinterpret_cast<const f32x4*>((kc & 1) ? buf_c : buf_b);
+    f32x4* nxt = reinterpret_cast<f32x4*>((kc & 1) ? buf_b : buf_c);
+    const bool more = kc + 1 < nkc;
+    // next slice and next feature pieces: asynchronous loads pinned here (inline assembly, see stage_fetch);
+    // the last iteration re-reads its own slice into the idle buffer
+    {
+      const f32x4* nsrc = w1 + (size_t)(more ? kc + 1 : kc) * kL1Units;
+#pragma unroll
+      for (int i = 0; i < kL1PerThread; ++i) {
+        const f32x4* p = nsrc + tid + i * kMfThreads;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wst[i]) : "v"(p) : "memory");
+      }
+      const int kb = kL1Chunk * (more ? kc + 1 : kc);
+#pragma unroll
+      for (int s = 0; s < kL1Chunk / 16; ++s) {
+        const int k0 = kb + 16 * s + 8 * g;
+        const uint16_t* p = row + (k0 < d ? kb + 16 * s : 0);          // out of range: any valid address, zeroed below
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(xn[s]) : "v"(p) : "memory");
+      }
+    }
+#pragma unroll
+    for (int hb = 0; hb < kMlpH / 32; ++hb) {
+#pragma unroll
+      for (int s = 0; s < kL1Chunk / 16; ++s) {
+        const f32x4 af = cur[(hb * 4 + s) * 64 + lane];
+        hacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(xs[s]), hacc[hb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the fragment reads of later hidden blocks from piling up in registers
+    }
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(wst[0]), "+v"(wst[1]), "+v"(wst[2]), "+v"(wst[3]), "+v"(xn[0]), "+v"(xn[1]), "+v"(xn[2]), "+v"(xn[3])
+                 :
+                 : "memory");
+#pragma unroll
+    for (int i = 0; i < kL1PerThread; ++i) nxt[tid + i * kMfThreads] = wst[i];
+    {
+      const int kb = kL1Chunk * (kc + 1);
+#pragma unroll
+      for (int s = 0; s < kL1Chunk / 16; ++s) {
+        const bool in = more && (kb + 16 * s + 8 * g < d);
+        xs[s] = in ? xn[s] : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- bias, ReLU, per-request scale, split into half-precision hi + lo ----
+  // hacc[hb][v] of lane (r, g) is hidden unit 32 hb + 8 (v/4) + 4 g + v%4 of request r
+  const float4* b1p = reinterpret_cast<const float4*>(w1p + w1_off[a] + (size_t)nkc * kL1Units * 16);   // padded to kMlpH
+  float amax = 0.f;
+#pragma unroll
+  for (int hb = 0; hb < kMlpH / 32; ++hb) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 bq = b1p[8 * hb + 2 * q + g];
+      hacc[hb][4 * q + 0] = fmaxf(hacc[hb][4 * q + 0] + bq.x, 0.f);
+      hacc[hb][4 * q + 1] = fmaxf(hacc[hb][4 * q + 1] + bq.y, 0.f);
+      hacc[hb][4 * q + 2] = fmaxf(hacc[hb][4 * q + 2] + bq.z, 0.f);
+      hacc[hb][4 * q + 3] = fmaxf(hacc[hb][4 * q + 3] + bq.w, 0.f);
+      amax = fmaxf(amax, fmaxf(fmaxf(hacc[hb][4 * q + 0], hacc[hb][4 * q + 1]),
+                               fmaxf(hacc[hb][4 * q + 2], hacc[hb][4 * q + 3])));
+    }
+  }
+  amax = fmaxf(amax, other_half(amax, g));
+  int ex = 0;
+  if (amax >= 1e-30f && amax <= 3e38f) ex = kSplitExp - (int)(((__float_as_uint(amax) >> 23) & 0xffu) - 126u);
+  const float hs = __uint_as_float((uint32_t)(127 + ex) << 23);
+  const float unscale = __uint_as_float((uint32_t)(127 - ex) << 23) * w_unscale[a];
+  f16x8 xh[D / 16], xl[D / 16];
+#pragma unroll
+  for (int hb = 0; hb < kMlpH / 32; ++hb) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      _Float16 hi, lo;
+      split_f16(hacc[hb][v] * hs, hi, lo);
+      xh[2 * hb + (v >> 3)][v & 7] = hi;
+      xl[2 * hb + (v >> 3)][v & 7] = lo;
+    }
+  }
+
+  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, CT, C, M, pos, id, valid, Dl, wt,
+                                  sortkey, logits_out);
+}
+
+}  // namespace sp

@@ -80,8 +80,17 @@ inline int host_scale_exponent(float vmax) {
   return ew;
 }
 
+// Which input index k a weight unit holds at (k-step s, lane half g, element e).  kMapRows: the lane
+// half owns one half of the input row (features loaded from memory).  kMapTile: the input comes out of
+// a previous 32x32 MFMA tile, where lane half g owns rows 8q + 4g + j of every block of 32.
+constexpr int kMapRows = 0, kMapTile = 1;
+template <int D, int KMAP>
+inline int split_k_index(int s, int g, int e) {
+  return KMAP == kMapRows ? g * (D / 2) + 8 * s + e : 32 * (s / 2) + 8 * (2 * (s % 2) + e / 4) + 4 * g + e % 4;
+}
+
 // Host-side packing of one application's head (called at context creation).  Returns 2^-ew.
-template <int D>
+template <int D, int KMAP>
 inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/, const float* acc /*[M,C]*/, int d,
                                int C, int M, unsigned char* out /*[CT * kBytes]*/) {
   using SB = SplitBlock<D>;
@@ -97,7 +106,7 @@ inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/,
     for (int s = 0; s < D / 16; ++s)
       for (int lane = 0; lane < 64; ++lane)
         for (int e = 0; e < 8; ++e) {
-          const int k = (lane / 32) * (D / 2) + 8 * s + e, cls = 32 * ct + lane % 32;
+          const int k = split_k_index<D, KMAP>(s, lane / 32, e), cls = 32 * ct + lane % 32;
           const float v = (k < d && cls < C) ? W[(size_t)k * C + cls] * ws : 0.f;
           uint16_t hi, lo;
           host_split(v, hi, lo);
@@ -294,6 +303,111 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   }
 }
 
+// Class tiles and epilogue shared by the scoring kernels: given the wavefront's 32 requests as split
+// half-precision inputs (xh, xl; logits = unscale * W' x' + b), walk the application's packed blocks,
+// then EA, variance, key.  buf_a already holds (or is receiving by DMA) block 0; the caller has not yet
+// synchronised the workgroup on it.
+template <int D, bool DUMP>
+__device__ __forceinline__ void class_tiles_and_finish(
+    const Tables& tb, const Window& w, float4* buf_a, float4* buf_b, float4* buf_c, const float4* __restrict__ src,
+    const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale, int CT, int C, int M, int pos, int id,
+    bool valid, const float* __restrict__ Dl, const float* __restrict__ wt, uint32_t* __restrict__ sortkey,
+    float* __restrict__ logits_out) {
+  using SB = SplitBlock<D>;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  __syncthreads();
+
+  float m2 = kNegBig;                                    // running maximum, in units of log2
+  f32x16 eacc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
+  const int64_t dump_row = (int64_t)id * tb.Cmax;
+
+  // The two wavefronts that share a SIMD run half a tile apart: wavefronts 0..3 do the matrix phase of
+  // tile t while wavefronts 4..7 do the softmax phase of tile t-1, then they swap, so the matrix cores
+  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 is fetched into the third
+  // buffer in two halves, one per phase.
+  const bool late = wave >= kMfWaves / 2;
+  f32x16 acc;
+#define SP_TILE(T, CUR, NXT, PRV)                                                                              \
+  if ((T) < CT) {                                                                                              \
+    const bool more = (T) + 1 < CT;                                                                            \
+    const float4* nsrc = src + (size_t)(more ? (T) + 1 : (T)) * SB::kUnits;                                    \
+    stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
+    if (!late) {                                                                                               \
+      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
+    } else if ((T) > 0) {                                                                                      \
+      softmax_phase<D, DUMP>(PRV, acc, unscale, eacc, m2, (T) - 1, C, g, lane, valid, dump_row, logits_out);   \
+    }                                                                                                          \
+    stage_park<D, 0>(NXT, stg, tid);      /* (after the last tile: a copy nobody reads) */                     \
+    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing read in the next phase was written here */ \
+    stage_fetch<D, 1>(nsrc, stg, tid);                                                                         \
+    if (!late) {                                                                                               \
+      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+    } else {                                                                                                   \
+      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
+    }                                                                                                          \
+    stage_park<D, 1>(NXT, stg, tid);                                                                           \
+    __syncthreads();                       /* block T+1 is complete in LDS */                                  \
+  }
+  StageRegs<D> stg;
+  stg.v[0] = stg.v[1] = stg.v[2] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t0 = 0; t0 < CT; t0 += 3) {
+    SP_TILE(t0, buf_a, buf_b, buf_c)
+    SP_TILE(t0 + 1, buf_b, buf_c, buf_a)
+    SP_TILE(t0 + 2, buf_c, buf_a, buf_b)
+  }
+#undef SP_TILE
+  if (late) {
+    const int last = (CT - 1) % 3;
+    const float4* lb = last == 0 ? buf_a : (last == 1 ? buf_b : buf_c);
+    softmax_phase<D, DUMP>(lb, acc, unscale, eacc, m2, CT - 1, C, g, lane, valid, dump_row, logits_out);
+  }
+  if (DUMP) return;
+
+  // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
+  // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
+  const float ssum = __shfl(eacc[8], r);
+  const float inv = 1.0f / ssum;
+  float ea[8];
+  float part = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    ea[v] = (m < M) ? eacc[v] * inv : 0.f;
+    part += ea[v];
+  }
+  const float mean = (part + __shfl_xor(part, 32)) / (float)M;
+  float vpart = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    const float dv = ea[v] - mean;
+    vpart += (m < M) ? dv * dv : 0.f;
+  }
+  const float var = (vpart + __shfl_xor(vpart, 32)) / (float)M;
+  if (!valid) return;
+  float* rowo = w.ea + (int64_t)id * tb.Mmax;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    if (m < tb.Mmax) rowo[m] = ea[v];
+  }
+  if (g == 0) {
+    const float Di = Dl[id], wi = wt[id];
+    uint32_t err = 0;
+    if (!(Di > 0.f)) err |= kErrDeadline;
+    if (!(wi >= 0.f)) err |= kErrWeight;
+    if (err) atomicOr(&w.st->err, err);
+    const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
+    w.key[id] = key;
+    sortkey[pos] = ~__float_as_uint(key);
+    w.D_g[pos] = Di;
+    w.w_g[pos] = wi;
+  }
+}
+
 template <int D, bool DUMP>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
@@ -392,96 +506,8 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       xl[q >> 3][q & 7] = lo;
     }
   }
-  __syncthreads();
-
-  float m2 = kNegBig;                                    // running maximum, in units of log2
-  f32x16 eacc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
-  const int64_t dump_row = (int64_t)id * tb.Cmax;
-
-  // The two wavefronts that share a SIMD run half a tile apart: wavefronts 0..3 do the matrix phase of
-  // tile t while wavefronts 4..7 do the softmax phase of tile t-1, then they swap, so the matrix cores
-  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 is fetched into the third
-  // buffer in two halves, one per phase.
-  const bool late = wave >= kMfWaves / 2;
-  f32x16 acc;
-#define SP_TILE(T, CUR, NXT, PRV)                                                                              \
-  if ((T) < CT) {                                                                                              \
-    const bool more = (T) + 1 < CT;                                                                            \
-    const float4* nsrc = src + (size_t)(more ? (T) + 1 : (T)) * SB::kUnits;                                    \
-    stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
-    if (!late) {                                                                                               \
-      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
-    } else if ((T) > 0) {                                                                                      \
-      softmax_phase<D, DUMP>(PRV, acc, unscale, eacc, m2, (T) - 1, C, g, lane, valid, dump_row, logits_out);   \
-    }                                                                                                          \
-    stage_park<D, 0>(NXT, stg, tid);      /* (after the last tile: a copy nobody reads) */                     \
-    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing read in the next phase was written here */ \
-    stage_fetch<D, 1>(nsrc, stg, tid);                                                                         \
-    if (!late) {                                                                                               \
-      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
-    } else {                                                                                                   \
-      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
-    }                                                                                                          \
-    stage_park<D, 1>(NXT, stg, tid);                                                                           \
-    __syncthreads();                       /* block T+1 is complete in LDS */                                  \
-  }
-  StageRegs<D> stg;
-  stg.v[0] = stg.v[1] = stg.v[2] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int t0 = 0; t0 < CT; t0 += 3) {
-    SP_TILE(t0, buf_a, buf_b, buf_c)
-    SP_TILE(t0 + 1, buf_b, buf_c, buf_a)
-    SP_TILE(t0 + 2, buf_c, buf_a, buf_b)
-  }
-#undef SP_TILE
-  if (late) {
-    const int last = (CT - 1) % 3;
-    const float4* lb = last == 0 ? buf_a : (last == 1 ? buf_b : buf_c);
-    softmax_phase<D, DUMP>(lb, acc, unscale, eacc, m2, CT - 1, C, g, lane, valid, dump_row, logits_out);
-  }
-  if (DUMP) return;
-
-  // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
-  // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
-  const float ssum = __shfl(eacc[8], r);
-  const float inv = 1.0f / ssum;
-  float ea[8];
-  float part = 0.f;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    ea[v] = (m < M) ? eacc[v] * inv : 0.f;
-    part += ea[v];
-  }
-  const float mean = (part + __shfl_xor(part, 32)) / (float)M;
-  float vpart = 0.f;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    const float dv = ea[v] - mean;
-    vpart += (m < M) ? dv * dv : 0.f;
-  }
-  const float var = (vpart + __shfl_xor(vpart, 32)) / (float)M;
-  if (!valid) return;
-  float* rowo = w.ea + (int64_t)id * tb.Mmax;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    if (m < tb.Mmax) rowo[m] = ea[v];
-  }
-  if (g == 0) {
-    const float Di = Dl[id], wi = wt[id];
-    uint32_t err = 0;
-    if (!(Di > 0.f)) err |= kErrDeadline;
-    if (!(wi >= 0.f)) err |= kErrWeight;
-    if (err) atomicOr(&w.st->err, err);
-    const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
-    w.key[id] = key;
-    sortkey[pos] = ~__float_as_uint(key);
-    w.D_g[pos] = Di;
-    w.w_g[pos] = wi;
-  }
+  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, CT, C, M, pos, id, valid, Dl, wt,
+                                  sortkey, logits_out);
 }
 
 }  // namespace sp
