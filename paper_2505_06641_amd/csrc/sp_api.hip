@@ -15,6 +15,7 @@
 #include "sp_score_generic.h"
 #include "sp_score_split.h"
 #include "sp_score_mlp.h"
+#include "sp_rounds_persist.h"
 #include "sp_sort.h"
 
 using namespace sp;
@@ -49,6 +50,13 @@ struct sp_ctx {
   bool mlp_bf16 = false;             // bf16 MLP heads run on the matrix-core MLP kernel
   unsigned char* w1p = nullptr;      // packed layer-1 slices for that kernel
   int64_t* w1_off = nullptr;         // [A] byte offsets
+  // all rounds of a chunk in one cooperative launch, when every (application, variant) pair fits on the device at once
+  bool persist = false;
+  Persist ps{};
+  uint32_t gen_base = 0;             // slot generations handed out so far
+  long long* h_ticks = nullptr;      // pinned mirror of ps.ticks
+  double tick_ms = 0.0;              // milliseconds per timestamp tick
+  std::vector<float> round_ms;       // per-round latencies of the last timed sp_schedule on that path
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -188,6 +196,7 @@ sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
 
 sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p);
 sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p);
+sp_status setup_persist(sp_ctx* c, const sp_profile* p);
 
 sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   const int A = p->n_apps, B = p->max_batch;
@@ -280,6 +289,7 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   SP_HIP(c, hipHostMalloc((void**)&c->h_state, sizeof(State), hipHostMallocDefault));
   std::memset(c->h_state, 0, sizeof(State));
   SP_HIP(c, hipMemset(w.st, 0, sizeof(State)));
+  if ((s = setup_persist(c, p)) != SP_OK) return s;
   if (c->score_lds > 64 * 1024) {
     const int bytes = (int)c->score_lds;
 #define SP_SET_LDS(T, MT) \
@@ -346,6 +356,72 @@ sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_upload(c, &c->blocks, h2)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->block_off, off2)) != SP_OK) return s;
   if ((s = dev_upload(c, &c->w_unscale, unscale)) != SP_OK) return s;
+  return SP_OK;
+}
+
+
+// The one-launch rounds path needs every (application, variant) pair plus the commit workgroup resident at
+// once; contexts too large for that keep the two-kernels-per-round path.
+sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
+  c->persist = false;
+  const int A = p->n_apps;
+  std::vector<int32_t> pa, pm;
+  for (int a = 0; a < A; ++a)
+    for (int m = 0; m < p->n_models[a]; ++m) { pa.push_back(a); pm.push_back(m); }
+  const size_t n_pairs = pa.size();
+  const size_t ring = (size_t)kPersistRounds * A * c->B;
+  if (n_pairs == 0 || n_pairs > 4096 || ring > ((size_t)32 << 20)) return SP_OK;
+  int coop = 0, cus = 0, per_cu = 0, rate_khz = 0;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, c->device) != hipSuccess || !coop) return SP_OK;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) return SP_OK;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent, kRoundThreads, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    return SP_OK;
+  }
+  if ((size_t)per_cu * (size_t)cus < n_pairs + 2) return SP_OK;
+  if (hipDeviceGetAttribute(&rate_khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess || rate_khz <= 0)
+    rate_khz = 100000;
+  c->tick_ms = 1.0 / (double)rate_khz;
+  Persist& ps = c->ps;
+  int32_t *d_pa = nullptr, *d_pm = nullptr;
+  sp_status s;
+  if ((s = dev_upload(c, &d_pa, pa)) != SP_OK) return s;
+  if ((s = dev_upload(c, &d_pm, pm)) != SP_OK) return s;
+  ps.pair_app = d_pa; ps.pair_model = d_pm; ps.n_pairs = (int32_t)n_pairs;
+  if ((s = dev_alloc(c, &ps.slots, 4 * n_pairs)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &ps.ring, ring)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &ps.dec, kPersistRounds)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &ps.decision, 4)) != SP_OK) return s;
+  SP_HIP(c, hipMemset(ps.decision, 0, 4 * 8));
+  if ((s = dev_alloc(c, &ps.ticks, kPersistRounds + 1)) != SP_OK) return s;
+  SP_HIP(c, hipMemset(ps.slots, 0, 4 * n_pairs * 8));
+  SP_HIP(c, hipMemset(ps.ring, 0, ring * 8));
+  SP_HIP(c, hipMemset(ps.dec, 0, kPersistRounds * 8));
+  SP_HIP(c, hipMemset(ps.ticks, 0, (kPersistRounds + 1) * 8));
+  SP_HIP(c, hipHostMalloc((void**)&c->h_ticks, (kPersistRounds + 1) * sizeof(long long), hipHostMallocDefault));
+  c->gen_base = 0;
+  c->persist = true;
+  return SP_OK;
+}
+
+void fill_u64(hipStream_t s, unsigned long long* p, size_t n) {
+  hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, (int64_t)n, 0ull);
+}
+
+// Up to kPersistRounds rounds in one cooperative launch.
+sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
+  Persist& ps = c->ps;
+  if (c->gen_base + (uint32_t)n_rounds + 2u >= kGenMask) {       // generation numbers about to wrap: start over
+    fill_u64(s, ps.slots, 4 * (size_t)ps.n_pairs);
+    fill_u64(s, ps.decision, 4);
+    fill_u64(s, ps.ring, (size_t)kPersistRounds * c->A * c->B);
+    c->gen_base = 0;
+  }
+  ps.n_rounds = n_rounds;
+  ps.gen_base = c->gen_base;
+  c->gen_base += (uint32_t)n_rounds;
+  void* args[] = {(void*)&c->tb, (void*)&c->w, (void*)&ps};
+  SP_HIP(c, hipLaunchCooperativeKernel((const void*)k_rounds_persistent, dim3(ps.n_pairs + 2), dim3(kRoundThreads), args, 0, s));
   return SP_OK;
 }
 
@@ -437,6 +513,15 @@ sp_status fetch_state(sp_ctx* c, hipStream_t s) {
   SP_HIP(c, hipGetLastError());
   c->rounds_done = c->h_state->round;
   c->done = c->h_state->done != 0;
+  if (c->h_state->err & kErrSync) {
+    // resident workgroups lost each other: leave the exchange buffers clean and stop using that path
+    c->hip_err = "rounds kernel: a wait between workgroups ran out";
+    fill_u64(s, c->ps.slots, 4 * (size_t)c->ps.n_pairs);
+    fill_u64(s, c->ps.dec, kPersistRounds);
+    (void)hipStreamSynchronize(s);
+    c->persist = false;
+    return SP_EDEVICE;
+  }
   return c->h_state->err ? SP_EINVAL : SP_OK;
 }
 
@@ -474,6 +559,7 @@ void sp_destroy(sp_ctx* c) {
   (void)hipDeviceSynchronize();
   for (void* p : c->dev_allocs) (void)hipFree(p);
   if (c->h_state) (void)hipHostFree(c->h_state);
+  if (c->h_ticks) (void)hipHostFree(c->h_ticks);
   for (hipEvent_t e : c->ev)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->round_ev) (void)hipEventDestroy(e);
@@ -584,18 +670,30 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   c->n_round_ev = 0;
   c->timed_rounds = false;
   if (tm) SP_HIP(c, hipEventRecord(c->ev[4], s));
+  c->round_ms.clear();
   while (!c->done) {
-    int chunk = 64;
+    int chunk = c->persist ? kPersistRounds : 64;
     if (max_rounds > 0) chunk = std::min(chunk, start + max_rounds - c->rounds_done);
     if (chunk <= 0) break;
-    for (int i = 0; i < chunk; ++i) {
-      launch_round(c, s, nullptr, nullptr);
-      if (tm && c->timing_rounds && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
+    const bool persist = c->persist;
+    const int32_t before = c->rounds_done;
+    if (persist) {
+      if ((st = launch_rounds_persistent(c, s, chunk)) != SP_OK) return st;
+      if (tm && c->timing_rounds)
+        SP_HIP(c, hipMemcpyAsync(c->h_ticks, c->ps.ticks, (kPersistRounds + 1) * sizeof(long long), hipMemcpyDeviceToHost, s));
+    } else {
+      for (int i = 0; i < chunk; ++i) {
+        launch_round(c, s, nullptr, nullptr);
+        if (tm && c->timing_rounds && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
+      }
     }
     if (tm) SP_HIP(c, hipEventRecord(c->ev[5], s));
     st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
     fetched = true;
     if (st != SP_OK) return st;
+    if (persist && tm && c->timing_rounds)
+      for (int i = 0; i < c->rounds_done - before; ++i)
+        c->round_ms.push_back((float)((double)(c->h_ticks[i + 1] - c->h_ticks[i]) * c->tick_ms));
   }
   if (!fetched && (st = fetch_state(c, s)) != SP_OK) return st;
   c->timed_rounds = tm && fetched;
@@ -692,7 +790,7 @@ sp_status sp_get_timing(sp_ctx* c, sp_timing* out) {
   if (c->timed_rounds) {
     SP_HIP(c, hipEventSynchronize(c->ev[5]));
     SP_HIP(c, hipEventElapsedTime(&t.rounds_ms, c->ev[4], c->ev[5]));
-    t.n_rounds_timed = c->n_round_ev;
+    t.n_rounds_timed = c->round_ms.empty() ? c->n_round_ev : (int32_t)c->round_ms.size();
   }
   *out = t;
   return SP_OK;
@@ -703,6 +801,12 @@ sp_status sp_get_round_times(sp_ctx* c, float* ms_out, int32_t capacity, int32_t
   if (!c->timing || !c->timed_rounds) return SP_ESTATE;
   DeviceGuard g(c->device);
   if (!g.ok) return SP_EDEVICE;
+  if (!c->round_ms.empty()) {          // the one-launch path times its rounds itself
+    const int n = std::min(capacity, (int)c->round_ms.size());
+    for (int i = 0; i < n; ++i) ms_out[i] = c->round_ms[i];
+    *n_out = n;
+    return SP_OK;
+  }
   const int n = std::min(capacity, c->n_round_ev);
   for (int i = 0; i < n; ++i) {
     SP_HIP(c, hipEventSynchronize(c->round_ev[i]));

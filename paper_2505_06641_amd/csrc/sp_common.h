@@ -13,6 +13,7 @@ constexpr int kWave = 64;
 constexpr uint32_t kErrApp = 1u;
 constexpr uint32_t kErrDeadline = 2u;
 constexpr uint32_t kErrWeight = 4u;
+constexpr uint32_t kErrSync = 8u;       // a bounded wait between resident workgroups ran out
 
 // Immutable per-context tables (device pointers).
 struct Tables {

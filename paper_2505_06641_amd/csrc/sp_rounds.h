@@ -195,6 +195,35 @@ __device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
   return scratch[0];
 }
 
+// Members of one batch: outputs, pending flags and the three sums.  pos_of(j) gives the service position
+// of the j-th member.  All threads of the workgroup call it; the sums come back on every thread.
+template <class PosFn>
+__device__ __forceinline__ void commit_members(const Tables& tb, const Window& w, int a, int m, int b, int r,
+                                               int next_order, double E, PosFn pos_of, int32_t* ids_out,
+                                               double* dsum, double& wu, double& su, double& viol) {
+  const int kind = tb.penalty[a];
+  wu = 0.0; su = 0.0; viol = 0.0;
+  for (int j = threadIdx.x; j < b; j += kRoundThreads) {
+    const int pos = pos_of(j);
+    const int id = w.id_s[pos];
+    const float D = w.D_s[pos];
+    const float u = w.ea[(int64_t)id * tb.Mmax + m] * one_minus_penalty(kind, D, 1.0f / D, E);
+    w.model[id] = m;
+    w.round_of[id] = r;
+    w.order_of[id] = next_order + j;
+    w.util[id] = u;
+    w.alive_s[pos] = 0;
+    w.last_ids[j] = id;
+    if (ids_out) ids_out[j] = id;
+    wu += (double)w.w_s[pos] * (double)u;
+    su += (double)u;
+    viol += fmax(0.0, E - (double)D);
+  }
+  wu = block_sum_f64(wu, dsum);
+  su = block_sum_f64(su, dsum);
+  viol = block_sum_f64(viol, dsum);
+}
+
 __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Window w, int32_t* __restrict__ ids_out) {
   __shared__ unsigned long long red[kRoundThreads / 64];
   __shared__ double dsum[kRoundThreads];
@@ -218,31 +247,13 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   const int b = (int)(cid % (uint32_t)B) + 1;
   const int am = (int)(cid / (uint32_t)B);
   const int m = am % tb.Mmax, a = am / tb.Mmax;
-  const int kind = tb.penalty[a];
   const int r = st->round;
   const double t = st->t;
   const int next_order = st->next_order;
   const double E = t + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
-  double wu = 0.0, su = 0.0, viol = 0.0;
-  for (int j = tid; j < b; j += kRoundThreads) {
-    const int pos = w.win_pos[a * B + j];
-    const int id = w.id_s[pos];
-    const float D = w.D_s[pos];
-    const float u = w.ea[(int64_t)id * tb.Mmax + m] * one_minus_penalty(kind, D, 1.0f / D, E);
-    w.model[id] = m;
-    w.round_of[id] = r;
-    w.order_of[id] = next_order + j;
-    w.util[id] = u;
-    w.alive_s[pos] = 0;
-    w.last_ids[j] = id;
-    if (ids_out) ids_out[j] = id;
-    wu += (double)w.w_s[pos] * (double)u;
-    su += (double)u;
-    viol += fmax(0.0, E - (double)D);
-  }
-  wu = block_sum_f64(wu, dsum);
-  su = block_sum_f64(su, dsum);
-  viol = block_sum_f64(viol, dsum);
+  double wu, su, viol;
+  const int32_t* row = w.win_pos + a * B;
+  commit_members(tb, w, a, m, b, r, next_order, E, [&](int j) { return row[j]; }, ids_out, dsum, wu, su, viol);
   if (tid == 0) {
     Decision dc;
     dc.app = a; dc.model = m; dc.batch = b; dc.round = r;

@@ -1,0 +1,408 @@
+// All greedy rounds of a chunk in one launch (Alg. 1 generalised to batch-capped rounds; eq. (2),
+// eq. (13), eq. (1) as in sp_rounds.h, which this kernel reproduces decision for decision).
+//
+// One workgroup per (application, variant) pair stays resident for the whole chunk; two more take the
+// maximum over the pairs and do the commits.  What a round costs on the two-kernel path is mostly latency: two kernel
+// boundaries, the walk over the service order and the gathers behind it.  Here
+//   * each pair keeps its application's candidate window in LDS between rounds, with as many look-ahead
+//     entries behind it as the window is long.  A round removes the entries the previous decision
+//     consumed (always a prefix: the greedy takes the first b live requests) and those whose penalty
+//     has reached 1 at the new clock (they never come back: the clock only advances), and goes to
+//     memory only when fewer than B entries remain while the application still has unvisited requests.
+//     Every position of the service order is visited once per launch, not once per round;
+//   * the arg max over all pairs goes through one slot per pair and a reducing workgroup: every pair
+//     publishes its best candidate, the reducer polls the slots (one per thread), takes the maximum and
+//     publishes the decision, which one thread of every pair polls.  Slots and the decision are pairs of
+//     64-bit words, each carrying the generation number of the round it belongs to, written and polled
+//     with relaxed device-scope atomics: a word is valid exactly when its generation matches, so no
+//     fence is needed and a stale value can never be mistaken for the current one.  Both are double
+//     buffered by generation parity (nobody can be more than one round ahead of anybody else: the
+//     reducer needs every pair's slot of a round, every pair needs the reducer's decision of it);
+//   * clock, round counter and window shifts follow from the decision and are replicated in every pair;
+//   * the commit workgroup receives each decision through a ring entry, and the members of the chosen
+//     batch through a ring of generation-tagged window positions written by the chosen application's
+//     first pair, so the commits (outputs, totals, decision log) run beside the next round's scoring.
+// All waits are bounded: a wait that runs out raises kErrSync and every workgroup leaves its loop.
+// The launch must be cooperative (all workgroups resident at once).
+#pragma once
+#include "sp_rounds.h"
+
+namespace sp {
+
+constexpr int kWinCap = 2 * kMaxBatch;          // window + look-ahead entries, one per thread
+constexpr int kPersistRounds = 64;              // rounds per launch (ring depth)
+constexpr int kSpinLimit = 1 << 20;             // polls before a wait is given up (about a second)
+constexpr uint32_t kGenMask = 0x7FFFFFu;        // generation bits carried in a slot's first word
+static_assert(kWinCap <= kRoundThreads, "one window entry per thread");
+
+struct Persist {
+  const int32_t* pair_app;      // [n_pairs] application of each pair
+  const int32_t* pair_model;    // [n_pairs] variant of each pair
+  int32_t n_pairs;
+  int32_t n_rounds;             // rounds this launch may run (<= kPersistRounds)
+  uint32_t gen_base;            // generations used by earlier launches
+  unsigned long long* slots;    // [2 (parity), n_pairs, 2 (word)]
+  unsigned long long* decision; // [2 (parity), 2 (word)]: latency bits << 32 | gen; (candidate id + 1, 0 = none) << 32 | gen
+  unsigned long long* ring;     // [kPersistRounds, A, B]: generation << 32 | service position
+  unsigned long long* dec;      // [kPersistRounds]: decision of each round, bit 63 set; zero once consumed
+  long long* ticks;             // [kPersistRounds + 1]: constant-rate timestamps, launch start then each decision
+};
+
+__device__ __forceinline__ unsigned long long ld_dev(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// slot word 0: score bits << 32 | generation (23 bits) << 9 | valid << 8 | (b - 1)
+// slot word 1: latency bits of the candidate (float) << 32 | generation (32 bits)
+__device__ __forceinline__ unsigned long long slot_word0(float score, uint32_t gen, bool valid, int b) {
+  return ((unsigned long long)__float_as_uint(score) << 32) | ((unsigned long long)(gen & kGenMask) << 9) |
+         (valid ? 0x100ull : 0ull) | (unsigned long long)((b - 1) & 0xff);
+}
+
+__device__ void persist_commit_loop(const Tables& tb, const Window& w, const Persist& ps, double* dsum,
+                                    unsigned long long* bcast) {
+  State* st = w.st;
+  const int tid = threadIdx.x;
+  int r = st->round, next_order = st->next_order, n_sched = st->n_sched;
+  double t = st->t, twu = st->total_wu, tu = st->total_u, tv = st->total_viol;
+  bool done = false, failed = false, any = false;
+  Decision last;
+  for (int rl = 0; rl < ps.n_rounds; ++rl) {
+    const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
+    if (tid == 0) {
+      unsigned long long v = 0ull;
+      for (int i = 0; i < kSpinLimit; ++i) {
+        v = ld_dev(ps.dec + rl);
+        if (v != 0ull) break;
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (v != 0ull) st_dev(ps.dec + rl, 0ull);
+      bcast[0] = v;
+    }
+    __syncthreads();
+    const unsigned long long v = bcast[0];
+    __syncthreads();
+    if (v == 0ull) { failed = true; break; }
+    const unsigned long long best = v & ~(1ull << 63);
+    if (best == 0ull) { done = true; break; }
+    const uint32_t cid = 0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull);
+    const float score = __uint_as_float((uint32_t)(best >> 32));
+    const int B = tb.B;
+    const int b = (int)(cid % (uint32_t)B) + 1;
+    const int am = (int)(cid / (uint32_t)B);
+    const int m = am % tb.Mmax, a = am / tb.Mmax;
+    const double E = t + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
+    const unsigned long long* row = ps.ring + ((size_t)rl * tb.A + a) * B;
+    bool lost = false;
+    double wu, su, viol;
+    commit_members(tb, w, a, m, b, r, next_order, E,
+                   [&](int j) {
+                     unsigned long long e = 0ull;
+                     for (int i = 0; i < kSpinLimit; ++i) {
+                       e = ld_dev(row + j);
+                       if ((uint32_t)(e >> 32) == gen) break;
+                       __builtin_amdgcn_s_sleep(4);
+                     }
+                     if ((uint32_t)(e >> 32) != gen) { lost = true; return 0; }   // position 0 exists: b >= 1 request
+                     return (int)(uint32_t)(e & 0xFFFFFFFFull);
+                   },
+                   nullptr, dsum, wu, su, viol);
+    if (__syncthreads_or(lost ? 1 : 0)) { failed = true; break; }
+    last.app = a; last.model = m; last.batch = b; last.round = r;
+    last.t_start = t; last.t_end = E; last.score = score; last.batch_utility = (float)wu;
+    any = true;
+    if (tid == 0 && r < w.log_cap) w.log[r] = last;
+    t = E; r += 1; next_order += b; n_sched += b;
+    twu += wu; tu += su; tv += viol;
+  }
+  if (tid == 0) {
+    st->t = t; st->round = r; st->next_order = next_order; st->n_sched = n_sched;
+    st->total_wu = twu; st->total_u = tu; st->total_viol = tv;
+    if (any) st->last = last;
+    if (done) st->done = 1;
+    if (failed) atomicOr(&st->err, kErrSync);
+  }
+}
+
+// The reducing workgroup: maximum over the pairs' slots of every round, published as the decision.
+__device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Persist& ps, unsigned long long* red,
+                                    float* lat_win, int* timed_out) {
+  const int tid = threadIdx.x;
+  const int B = tb.B;
+  const int my_slot = tid < ps.n_pairs ? tid : 0;
+  const int my_a = ps.pair_app[my_slot], my_m = ps.pair_model[my_slot];
+  if (tid == 0) {
+    *timed_out = 0;
+    ps.ticks[0] = wall_clock64();
+  }
+  __syncthreads();
+  for (int rl = 0; rl < ps.n_rounds; ++rl) {
+    const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
+    unsigned long long mine = 0ull;
+    float mine_lat = 0.f;
+    for (int i = tid; i < ps.n_pairs; i += kRoundThreads) {
+      const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + i) * 2;
+      unsigned long long v0 = 0ull, v1 = 0ull;
+      bool ok = false;
+      for (int k = 0; k < kSpinLimit; ++k) {
+        v0 = ld_dev(slot);
+        v1 = ld_dev(slot + 1);
+        ok = ((uint32_t)(v0 >> 9) & kGenMask) == (gen & kGenMask) && (uint32_t)(v1 & 0xFFFFFFFFull) == gen;
+        if (ok) break;
+        __builtin_amdgcn_s_sleep(1);
+      }
+      if (!ok) {
+        *timed_out = 1;
+      } else if (v0 & 0x100ull) {
+        const int pa = i == tid ? my_a : ps.pair_app[i], pm = i == tid ? my_m : ps.pair_model[i];
+        const uint32_t cid = (uint32_t)((pa * tb.Mmax + pm) * B) + (uint32_t)(v0 & 0xffull);
+        const unsigned long long pk = pack_candidate(__uint_as_float((uint32_t)(v0 >> 32)), cid);
+        if (pk > mine) { mine = pk; mine_lat = __uint_as_float((uint32_t)(v1 >> 32)); }
+      }
+    }
+    const unsigned long long all = block_max_u64(mine, red);
+    if (all != 0ull && mine == all) *lat_win = mine_lat;      // candidate ids are unique: one writer
+    __syncthreads();
+    if (*timed_out) {
+      if (tid == 0) atomicOr(&w.st->err, kErrSync);
+      break;
+    }
+    if (tid == 0) {
+      unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 2;
+      const uint32_t cidp1 = all != 0ull ? (0xFFFFFFFFu - (uint32_t)(all & 0xFFFFFFFFull)) + 1u : 0u;
+      st_dev(d, ((unsigned long long)__float_as_uint(all != 0ull ? *lat_win : 0.f) << 32) | (unsigned long long)gen);
+      st_dev(d + 1, ((unsigned long long)cidp1 << 32) | (unsigned long long)gen);
+      st_dev(ps.dec + rl, all | (1ull << 63));
+      ps.ticks[rl + 1] = wall_clock64();
+    }
+    if (all == 0ull) break;                                    // nothing live anywhere
+    __syncthreads();                                           // lat_win is rewritten next round
+  }
+}
+
+__global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, Window w, Persist ps) {
+  __shared__ int32_t win[kWinCap];
+  __shared__ float aj[kWinCap], Dj[kWinCap], invDj[kWinCap];
+  __shared__ float lat_s[kMaxBatch];
+  __shared__ int32_t wave_cnt[kRoundThreads / 64], keep_cnt[kRoundThreads / 64];
+  __shared__ unsigned long long red[kRoundThreads / 64];
+  __shared__ double dsum[kRoundThreads];
+  __shared__ float lat_win;
+  __shared__ uint32_t cid_win;
+  __shared__ int timed_out;
+  State* st = w.st;
+  if (st->done || st->err) return;          // the state is rewritten only when the commit workgroup ends
+  if ((int)blockIdx.x >= ps.n_pairs) {
+    if ((int)blockIdx.x == ps.n_pairs) persist_reduce_loop(tb, w, ps, red, &lat_win, &timed_out);
+    if ((int)blockIdx.x == ps.n_pairs + 1) persist_commit_loop(tb, w, ps, dsum, red);
+    return;
+  }
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pair = blockIdx.x;
+  const int a = ps.pair_app[pair], m = ps.pair_model[pair];
+  const int B = tb.B, cap = min(2 * B, kWinCap);
+  const int kind = tb.penalty[a];
+  const float lmin = tb.lmin[a];
+  const int seg_e = w.seg[a + 1];
+  int r = st->round;
+  double t = st->t;
+  int scan_end = w.head[(r & 1) * tb.A + a];     // everything before it is consumed or dead
+  int nb = 0, shift = 0;
+  for (int j = tid; j < B; j += kRoundThreads) lat_s[j] = tb.lat[((int64_t)a * tb.Mmax + m) * B + j];
+  if (tid == 0) timed_out = 0;
+  __syncthreads();
+
+  for (int rl = 0; rl < ps.n_rounds; ++rl) {
+    const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
+    const double E0 = t + (double)lmin;
+
+    // ---- drop what the last decision consumed and what has died since ----
+    {
+      const bool has = tid < nb;
+      int pos = 0;
+      float av = 0.f, dv = 1.f, iv = 0.f;
+      if (has) { pos = win[tid]; av = aj[tid]; dv = Dj[tid]; iv = invDj[tid]; }
+      const bool keep = has && tid >= shift && !is_dead(kind, dv, E0);
+      const unsigned long long bal = __ballot(keep);
+      if (lane == 0) keep_cnt[wave] = __popcll(bal);
+      __syncthreads();
+      int before = 0, total = 0;
+      for (int i = 0; i < kRoundThreads / 64; ++i) {
+        const int c = keep_cnt[i];
+        if (i < wave) before += c;
+        total += c;
+      }
+      if (total != nb) {
+        before += __popcll(bal & ((1ull << lane) - 1ull));
+        if (keep) { win[before] = pos; aj[before] = av; Dj[before] = dv; invDj[before] = iv; }
+        nb = total;
+      }
+      shift = 0;
+      __syncthreads();
+    }
+
+    // ---- fewer than B entries left: walk on through the service order ----
+    if (nb < B && scan_end < seg_e) {
+      const int nb_old = nb;
+      for (int step = 0; nb < cap && scan_end < seg_e; ++step) {
+        const int nq = step == 0 ? 1 : 4;                  // groups of 4 positions per thread
+        const int base = scan_end & ~3;
+        const int p0 = base + 4 * nq * tid;
+        uint32_t mask = 0;
+        if (p0 < seg_e) {
+          for (int q = 0; q < nq; ++q) {
+            const uint32_t alw = *reinterpret_cast<const uint32_t*>(w.alive_s + p0 + 4 * q);
+            const float4 dv = *reinterpret_cast<const float4*>(w.D_s + p0 + 4 * q);
+            const float dd[4] = {dv.x, dv.y, dv.z, dv.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int pos = p0 + 4 * q + j;
+              const bool live = ((alw >> (8 * j)) & 0xffu) != 0 && !is_dead(kind, dd[j], E0) && pos >= scan_end && pos < seg_e;
+              mask |= live ? (1u << (4 * q + j)) : 0u;
+            }
+          }
+        }
+        const int cnt = __popc(mask);
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int up = __shfl_up(incl, o);
+          if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_cnt[wave] = incl;
+        __syncthreads();
+        int before = nb, total = nb;
+        for (int i = 0; i < kRoundThreads / 64; ++i) {
+          if (i < wave) before += wave_cnt[i];
+          total += wave_cnt[i];
+        }
+        int rank = before + incl - cnt;
+        uint32_t mk = mask;
+        while (mk != 0 && rank < cap) {
+          const int j = __ffs((int)mk) - 1;
+          mk &= mk - 1;
+          win[rank++] = p0 + j;
+        }
+        __syncthreads();
+        if (total >= cap) {
+          scan_end = win[cap - 1] + 1;                     // the rest of this step is looked at again later
+          nb = cap;
+        } else {
+          scan_end = min(base + 4 * nq * kRoundThreads, seg_e);
+          nb = total;
+        }
+      }
+      for (int j = nb_old + tid; j < nb; j += kRoundThreads) {
+        const int pos = win[j];
+        const float D = w.D_s[pos];
+        aj[j] = w.key_s[pos] * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m];
+        Dj[j] = D;
+        invDj[j] = 1.0f / D;
+      }
+      __syncthreads();
+    }
+    const int nbe = min(nb, B);
+
+    // ---- the window's positions for the commit workgroup ----
+    if (m == 0 && tid < nbe)
+      st_dev(ps.ring + ((size_t)rl * tb.A + a) * B + tid, ((unsigned long long)gen << 32) | (unsigned long long)(uint32_t)win[tid]);
+
+    // ---- triangle, as in k_round_score ----
+    unsigned long long best = 0ull;
+    if (nbe > 0) {
+      const int sub = tid % kPairLanes, grp = tid / kPairLanes;
+      const int n_pairs_b = (B + 1) / 2;
+      for (int p = grp; p < n_pairs_b; p += kRoundThreads / kPairLanes) {
+        const int b1 = p + 1, b2 = B - p;
+        const double E1 = t + (double)lat_s[b1 - 1], E2 = t + (double)lat_s[b2 - 1];
+        const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
+        const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
+        const int n1 = b1 <= nbe ? b1 : 0, n2 = (b2 <= nbe && b2 != b1) ? b2 : 0;
+        float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int j = sub;
+        for (; j < n1 && j < n2; j += kPairLanes) {
+          const float av = aj[j], dv = Dj[j], iv = invDj[j];
+          s1 += av * one_minus_penalty_f32(kind, dv, iv, e1h, e1l);
+          s2 += av * one_minus_penalty_f32(kind, dv, iv, e2h, e2l);
+        }
+        for (; j < n1; j += kPairLanes) s1 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e1h, e1l);
+        for (; j + kPairLanes < n2; j += 2 * kPairLanes) {
+          s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
+          s3 += aj[j + kPairLanes] * one_minus_penalty_f32(kind, Dj[j + kPairLanes], invDj[j + kPairLanes], e2h, e2l);
+        }
+        if (j < n2) s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
+        s2 += s3;
+#pragma unroll
+        for (int o = 1; o < kPairLanes; o <<= 1) {
+          s1 += __shfl_xor(s1, o);
+          s2 += __shfl_xor(s2, o);
+        }
+        if (sub == 0) {
+          const uint32_t cid0 = (uint32_t)((a * tb.Mmax + m) * B);
+          if (n1 > 0) {
+            const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
+            best = pk > best ? pk : best;
+          }
+          if (n2 > 0) {
+            const unsigned long long pk = pack_candidate(s2, cid0 + (uint32_t)(b2 - 1));
+            best = pk > best ? pk : best;
+          }
+        }
+      }
+    }
+    best = block_max_u64(best, red);
+
+    // ---- publish this pair's best candidate ----
+    if (tid == 0) {
+      unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + pair) * 2;
+      const bool valid = best != 0ull;
+      const int b = valid ? (int)((0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull)) % (uint32_t)B) + 1 : 1;
+      st_dev(slot + 1, ((unsigned long long)__float_as_uint(lat_s[b - 1]) << 32) | (unsigned long long)gen);
+      st_dev(slot, slot_word0(__uint_as_float((uint32_t)(best >> 32)), gen, valid, b));
+    }
+
+    // ---- wait for the decision ----
+    if (tid == 0) {
+      const unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 2;
+      unsigned long long v0 = 0ull, v1 = 0ull;
+      bool ok = false;
+      for (int k = 0; k < kSpinLimit; ++k) {
+        v0 = ld_dev(d);
+        v1 = ld_dev(d + 1);
+        ok = (uint32_t)(v0 & 0xFFFFFFFFull) == gen && (uint32_t)(v1 & 0xFFFFFFFFull) == gen;
+        if (ok) break;
+        __builtin_amdgcn_s_sleep(1);
+      }
+      if (!ok) timed_out = 1;
+      lat_win = __uint_as_float((uint32_t)(v0 >> 32));
+      cid_win = (uint32_t)(v1 >> 32);
+    }
+    __syncthreads();
+    if (timed_out) {
+      if (tid == 0) atomicOr(&st->err, kErrSync);
+      break;
+    }
+    const uint32_t cidp1 = cid_win;
+    const float lat_sel = lat_win;
+    __syncthreads();                                         // both are rewritten next round
+    if (cidp1 == 0u) break;                                  // nothing live anywhere
+    const uint32_t cid = cidp1 - 1u;
+    const int bsel = (int)(cid % (uint32_t)B) + 1;
+    const int asel = (int)(cid / (uint32_t)B) / tb.Mmax;
+    shift = asel == a ? bsel : 0;
+    t = t + (double)lat_sel;
+    r += 1;
+  }
+  // first position of this application that may still be live, for whoever continues the window
+  if (m == 0 && tid == 0) w.head[(r & 1) * tb.A + a] = shift < nb ? win[shift] : scan_end;
+}
+
+__global__ void k_fill_u64(unsigned long long* p, int64_t n, unsigned long long v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace sp

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
   const int pos = seg_b + (tile - w.tile_start[a]) * kMfTile + wave * 32 + r;
   const bool valid = pos < seg_e;
   const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
-  const int d = tb.d, H = tb.H, C = tb.n_classes[a], M = tb.n_models[a];
+  const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];
   const int CT = (C + kClassTile - 1) / kClassTile;
   const int nkc = (d + kL1Chunk - 1) / kL1Chunk;
 
