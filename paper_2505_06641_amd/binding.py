@@ -21,6 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
+           "sp_rounds_in_one_launch",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -97,6 +98,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_max_models.restype = C.c_int32
     lib.sp_max_classes.argtypes = [vp]
     lib.sp_max_classes.restype = C.c_int32
+    lib.sp_rounds_in_one_launch.argtypes = [vp]
+    lib.sp_rounds_in_one_launch.restype = C.c_int32
     lib.sp_set_timing.argtypes = [vp, C.c_int32]
     lib.sp_set_timing.restype = C.c_int
     lib.sp_get_timing.argtypes = [vp, C.POINTER(sp_timing)]
@@ -188,6 +191,7 @@ class Context:
         self.h = h
         self.m_max = self.lib.sp_max_models(h)
         self.c_max = self.lib.sp_max_classes(h)
+        self.rounds_in_one_launch = bool(self.lib.sp_rounds_in_one_launch(h))
         self.n = 0
 
     def _check(self, rc, where, ok=(SP_OK,)):

@@ -832,5 +832,6 @@ const char* sp_strerror(sp_status s) {
 const char* sp_last_hip_error(const sp_ctx* c) { return c ? c->hip_err.c_str() : ""; }
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
+int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist) ? 1 : 0; }
 
 }  // extern "C"

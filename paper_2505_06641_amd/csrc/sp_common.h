@@ -115,24 +115,28 @@ __device__ __forceinline__ float one_minus_penalty(int kind, float D, float invD
 }
 
 // Same quantity with the completion time given as an unevaluated float pair E = e_hi + e_lo
-// (e_hi = float(E), e_lo = float(E - e_hi)), for inner loops that should stay in float32.
+// (e_hi = float(E), e_lo = float(E - e_hi)), for inner loops that should stay in float32; the penalty
+// kind is a template parameter so that those loops carry no branches.
 // l = (e_hi - D) + e_lo and r = (2D - e_hi) - e_lo: where E and D (or 2D) are within a factor two of
 // each other the first difference is exact (Sterbenz), so l and r carry E's full precision exactly
 // where cancellation would hurt; elsewhere their relative error is one rounding.  A rounded sum has
 // the sign of the exact sum, so l <= 0 (on time) and r <= 0 (penalty 1) are decided exactly as in
-// double precision.
-__device__ __forceinline__ float one_minus_penalty_f32(int kind, float D, float invD, float e_hi, float e_lo) {
+// double precision.  The sigmoid's denominator x^3 + y^3 is at least 1/4 (x + y = 1), so the
+// hardware reciprocal (1 ulp) is safe.
+template <int KIND>
+__device__ __forceinline__ float one_minus_penalty_f32(float D, float twoD, float invD, float e_hi, float e_lo) {
   const float l = (e_hi - D) + e_lo;
-  const float r = (2.0f * D - e_hi) - e_lo;
+  if (KIND == 0) return l <= 0.f ? 1.0f : 0.f;
+  const float r = (twoD - e_hi) - e_lo;
   float v;
-  if (kind == 1) {
+  if (KIND == 1) {
     v = r * invD;
   } else {
     const float x = l * invD, y = r * invD;
     const float y3 = y * y * y, x3 = x * x * x;
-    v = y3 * __frcp_rn(x3 + y3);
+    v = y3 * __builtin_amdgcn_rcpf(x3 + y3);
   }
-  v = (kind == 0 || r <= 0.f) ? 0.f : v;
+  v = r <= 0.f ? 0.f : v;
   return l <= 0.f ? 1.0f : v;
 }
 

@@ -41,9 +41,83 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
   return r;
 }
 
+// Score[a,m,b] for every batch size b over a candidate window of nb entries, and the best of them as a
+// packed candidate.  ent[j] = (key_j * EA[j,m], D_j, 1/D_j, 2 D_j); lat[b-1] = L[a][m][b].
+// Groups of kPairLanes lanes own the batch sizes (p+1, B-p), so all groups do the same amount of work;
+// both batch sizes of a pair run in the same loop (two independent chains per lane), and the completion
+// time of each batch size is carried as a float pair so that the loop stays in float32.
+// Every kernel that scores rounds calls this function: their scores agree bit for bit.
+template <int KIND>
+__device__ __forceinline__ unsigned long long triangle_best_kind(const float4* ent, const float* lat, int nb, int B,
+                                                                double t, uint32_t cid0, float* cube_out) {
+  const int tid = threadIdx.x;
+  const int sub = tid % kPairLanes, grp = tid / kPairLanes;
+  const int n_pairs = (B + 1) / 2;
+  unsigned long long best = 0ull;
+  for (int p = grp; p < n_pairs; p += kRoundThreads / kPairLanes) {
+    const int b1 = p + 1, b2 = B - p;                 // b1 <= b2; equal for the middle size of an odd B
+    const double E1 = t + (double)lat[b1 - 1], E2 = t + (double)lat[b2 - 1];
+    const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
+    const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
+    const int n1 = b1 <= nb ? b1 : 0, n2 = (b2 <= nb && b2 != b1) ? b2 : 0;
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int j = sub;
+    for (; j < n1 && j < n2; j += kPairLanes) {                 // both batch sizes use request j
+      const float4 e = ent[j];
+      s1 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e1h, e1l);
+      s2 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e2h, e2l);
+    }
+    for (; j < n1; j += kPairLanes) {
+      const float4 e = ent[j];
+      s1 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e1h, e1l);
+    }
+    for (; j + kPairLanes < n2; j += 2 * kPairLanes) {          // only the larger one: two requests per trip
+      const float4 e = ent[j], f = ent[j + kPairLanes];
+      s2 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e2h, e2l);
+      s3 += f.x * one_minus_penalty_f32<KIND>(f.y, f.w, f.z, e2h, e2l);
+    }
+    if (j < n2) {
+      const float4 e = ent[j];
+      s2 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e2h, e2l);
+    }
+    s2 += s3;
+#pragma unroll
+    for (int o = 1; o < kPairLanes; o <<= 1) {
+      s1 += __shfl_xor(s1, o);
+      s2 += __shfl_xor(s2, o);
+    }
+    if (sub == 0) {
+      if (n1 > 0) {
+        const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
+        best = pk > best ? pk : best;
+        if (cube_out) cube_out[cid0 + b1 - 1] = s1;
+      }
+      if (n2 > 0) {
+        const unsigned long long pk = pack_candidate(s2, cid0 + (uint32_t)(b2 - 1));
+        best = pk > best ? pk : best;
+        if (cube_out) cube_out[cid0 + b2 - 1] = s2;
+      }
+    }
+  }
+  return best;
+}
+
+__device__ __forceinline__ unsigned long long triangle_best(int kind, const float4* ent, const float* lat, int nb, int B,
+                                                           double t, uint32_t cid0, float* cube_out) {
+  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out);
+  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out);
+  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out);
+}
+
+// One window entry from the request at service position pos, for variant m.
+__device__ __forceinline__ float4 window_entry(const Tables& tb, const Window& w, int pos, int m) {
+  const float D = w.D_s[pos];
+  return make_float4(w.key_s[pos] * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m], D, 1.0f / D, 2.0f * D);
+}
+
 __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window w, float* __restrict__ cube_out) {
   __shared__ int32_t win[kMaxBatch];
-  __shared__ float aj[kMaxBatch], Dj[kMaxBatch], invDj[kMaxBatch];
+  __shared__ float4 ent[kMaxBatch];
   __shared__ int32_t wave_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
   const State* st = w.st;
@@ -124,61 +198,10 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     if (tid == 0) w.cand[blockIdx.x] = 0ull;
     return;
   }
-  for (int j = tid; j < nb; j += kRoundThreads) {
-    const int pos = win[j];
-    const float D = w.D_s[pos];
-    aj[j] = w.key_s[pos] * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m];
-    Dj[j] = D;
-    invDj[j] = 1.0f / D;
-  }
+  for (int j = tid; j < nb; j += kRoundThreads) ent[j] = window_entry(tb, w, win[j], m);
   __syncthreads();
-
-  // ---- triangle: groups of kPairLanes lanes own the batch sizes (p+1, B-p) ----
-  // Both batch sizes of a pair run in the same loop (two independent chains per lane), the completion
-  // time of each batch size is carried as a float pair so that the loop stays in float32.
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
-  const int sub = tid % kPairLanes, grp = tid / kPairLanes;
-  const int n_pairs = (B + 1) / 2;
-  unsigned long long best = 0ull;
-  for (int p = grp; p < n_pairs; p += kRoundThreads / kPairLanes) {
-    const int b1 = p + 1, b2 = B - p;                 // b1 <= b2; equal for the middle size of an odd B
-    const double E1 = t + (double)lat[b1 - 1], E2 = t + (double)lat[b2 - 1];
-    const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
-    const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
-    const int n1 = b1 <= nb ? b1 : 0, n2 = (b2 <= nb && b2 != b1) ? b2 : 0;
-    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    int j = sub;
-    for (; j < n1 && j < n2; j += kPairLanes) {                 // both batch sizes use request j
-      const float av = aj[j], dv = Dj[j], iv = invDj[j];
-      s1 += av * one_minus_penalty_f32(kind, dv, iv, e1h, e1l);
-      s2 += av * one_minus_penalty_f32(kind, dv, iv, e2h, e2l);
-    }
-    for (; j < n1; j += kPairLanes) s1 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e1h, e1l);
-    for (; j + kPairLanes < n2; j += 2 * kPairLanes) {                       // only the larger one: two requests per trip
-      s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
-      s3 += aj[j + kPairLanes] * one_minus_penalty_f32(kind, Dj[j + kPairLanes], invDj[j + kPairLanes], e2h, e2l);
-    }
-    if (j < n2) s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
-    s2 += s3;
-#pragma unroll
-    for (int o = 1; o < kPairLanes; o <<= 1) {
-      s1 += __shfl_xor(s1, o);
-      s2 += __shfl_xor(s2, o);
-    }
-    if (sub == 0) {
-      const uint32_t cid0 = (uint32_t)((a * tb.Mmax + m) * B);
-      if (n1 > 0) {
-        const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
-        best = pk > best ? pk : best;
-        if (cube_out) cube_out[cid0 + b1 - 1] = s1;
-      }
-      if (n2 > 0) {
-        const unsigned long long pk = pack_candidate(s2, cid0 + (uint32_t)(b2 - 1));
-        best = pk > best ? pk : best;
-        if (cube_out) cube_out[cid0 + b2 - 1] = s2;
-      }
-    }
-  }
+  unsigned long long best = triangle_best(kind, ent, lat, nb, B, t, (uint32_t)((a * tb.Mmax + m) * B), cube_out);
   best = block_max_u64(best, red);
   if (tid == 0) w.cand[blockIdx.x] = best;
 }

@@ -4,12 +4,13 @@
 // One workgroup per (application, variant) pair stays resident for the whole chunk; two more take the
 // maximum over the pairs and do the commits.  What a round costs on the two-kernel path is mostly latency: two kernel
 // boundaries, the walk over the service order and the gathers behind it.  Here
-//   * each pair keeps its application's candidate window in LDS between rounds, with as many look-ahead
-//     entries behind it as the window is long.  A round removes the entries the previous decision
-//     consumed (always a prefix: the greedy takes the first b live requests) and those whose penalty
-//     has reached 1 at the new clock (they never come back: the clock only advances), and goes to
-//     memory only when fewer than B entries remain while the application still has unvisited requests.
-//     Every position of the service order is visited once per launch, not once per round;
+//   * each pair keeps its application's candidate window in LDS between rounds, with look-ahead entries
+//     behind it (kWinCap in all).  A round removes the entries the previous decision consumed (always a
+//     prefix: the greedy takes the first b live requests) and those whose penalty has reached 1 at the
+//     new clock (they never come back: the clock only advances).  The walk over the service order that
+//     refills the look-ahead runs one step per round while the candidates are being exchanged; a round
+//     waits for it only when fewer than B entries remain while the application still has unvisited
+//     requests.  Every position of the service order is visited once per launch, not once per round;
 //   * the arg max over all pairs goes through one slot per pair and a reducing workgroup: every pair
 //     publishes its best candidate, the reducer polls the slots (one per thread), takes the maximum and
 //     publishes the decision, which one thread of every pair polls.  Slots and the decision are pairs of
@@ -183,9 +184,9 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
   }
 }
 
-__global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, Window w, Persist ps) {
+__global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables tb, Window w, Persist ps) {
   __shared__ int32_t win[kWinCap];
-  __shared__ float aj[kWinCap], Dj[kWinCap], invDj[kWinCap];
+  __shared__ float4 ent[kWinCap];
   __shared__ float lat_s[kMaxBatch];
   __shared__ int32_t wave_cnt[kRoundThreads / 64], keep_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int pair = blockIdx.x;
   const int a = ps.pair_app[pair], m = ps.pair_model[pair];
-  const int B = tb.B, cap = min(2 * B, kWinCap);
+  const int B = tb.B, cap = kWinCap;
   const int kind = tb.penalty[a];
   const float lmin = tb.lmin[a];
   const int seg_e = w.seg[a + 1];
@@ -223,9 +224,9 @@ __global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, 
     {
       const bool has = tid < nb;
       int pos = 0;
-      float av = 0.f, dv = 1.f, iv = 0.f;
-      if (has) { pos = win[tid]; av = aj[tid]; dv = Dj[tid]; iv = invDj[tid]; }
-      const bool keep = has && tid >= shift && !is_dead(kind, dv, E0);
+      float4 e = make_float4(0.f, 1.f, 0.f, 0.f);
+      if (has) { pos = win[tid]; e = ent[tid]; }
+      const bool keep = has && tid >= shift && !is_dead(kind, e.y, E0);
       const unsigned long long bal = __ballot(keep);
       if (lane == 0) keep_cnt[wave] = __popcll(bal);
       __syncthreads();
@@ -237,18 +238,20 @@ __global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, 
       }
       if (total != nb) {
         before += __popcll(bal & ((1ull << lane) - 1ull));
-        if (keep) { win[before] = pos; aj[before] = av; Dj[before] = dv; invDj[before] = iv; }
+        if (keep) { win[before] = pos; ent[before] = e; }
         nb = total;
       }
       shift = 0;
       __syncthreads();
     }
 
-    // ---- fewer than B entries left: walk on through the service order ----
-    if (nb < B && scan_end < seg_e) {
+    // Walks on through the service order from scan_end and appends the live requests it meets, for at
+    // most max_steps steps of 4 * nq positions per thread, until the window is full or the application's
+    // range ends.  Uniform over the workgroup.
+    auto walk = [&](int max_steps, int first_nq) {
       const int nb_old = nb;
-      for (int step = 0; nb < cap && scan_end < seg_e; ++step) {
-        const int nq = step == 0 ? 1 : 4;                  // groups of 4 positions per thread
+      for (int step = 0; step < max_steps && nb < cap && scan_end < seg_e; ++step) {
+        const int nq = step == 0 ? first_nq : 4;           // groups of 4 positions per thread
         const int base = scan_end & ~3;
         const int p0 = base + 4 * nq * tid;
         uint32_t mask = 0;
@@ -295,64 +298,21 @@ __global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, 
           nb = total;
         }
       }
-      for (int j = nb_old + tid; j < nb; j += kRoundThreads) {
-        const int pos = win[j];
-        const float D = w.D_s[pos];
-        aj[j] = w.key_s[pos] * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m];
-        Dj[j] = D;
-        invDj[j] = 1.0f / D;
-      }
+      for (int j = nb_old + tid; j < nb; j += kRoundThreads) ent[j] = window_entry(tb, w, win[j], m);
       __syncthreads();
-    }
+    };
+
+    // ---- fewer than B entries left: the round has to wait for the walk ----
+    if (nb < B && scan_end < seg_e) walk(1 << 30, 1);
     const int nbe = min(nb, B);
 
     // ---- the window's positions for the commit workgroup ----
     if (m == 0 && tid < nbe)
       st_dev(ps.ring + ((size_t)rl * tb.A + a) * B + tid, ((unsigned long long)gen << 32) | (unsigned long long)(uint32_t)win[tid]);
 
-    // ---- triangle, as in k_round_score ----
+    // ---- triangle: the same code as k_round_score ----
     unsigned long long best = 0ull;
-    if (nbe > 0) {
-      const int sub = tid % kPairLanes, grp = tid / kPairLanes;
-      const int n_pairs_b = (B + 1) / 2;
-      for (int p = grp; p < n_pairs_b; p += kRoundThreads / kPairLanes) {
-        const int b1 = p + 1, b2 = B - p;
-        const double E1 = t + (double)lat_s[b1 - 1], E2 = t + (double)lat_s[b2 - 1];
-        const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
-        const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
-        const int n1 = b1 <= nbe ? b1 : 0, n2 = (b2 <= nbe && b2 != b1) ? b2 : 0;
-        float s1 = 0.f, s2 = 0.f, s3 = 0.f;
-        int j = sub;
-        for (; j < n1 && j < n2; j += kPairLanes) {
-          const float av = aj[j], dv = Dj[j], iv = invDj[j];
-          s1 += av * one_minus_penalty_f32(kind, dv, iv, e1h, e1l);
-          s2 += av * one_minus_penalty_f32(kind, dv, iv, e2h, e2l);
-        }
-        for (; j < n1; j += kPairLanes) s1 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e1h, e1l);
-        for (; j + kPairLanes < n2; j += 2 * kPairLanes) {
-          s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
-          s3 += aj[j + kPairLanes] * one_minus_penalty_f32(kind, Dj[j + kPairLanes], invDj[j + kPairLanes], e2h, e2l);
-        }
-        if (j < n2) s2 += aj[j] * one_minus_penalty_f32(kind, Dj[j], invDj[j], e2h, e2l);
-        s2 += s3;
-#pragma unroll
-        for (int o = 1; o < kPairLanes; o <<= 1) {
-          s1 += __shfl_xor(s1, o);
-          s2 += __shfl_xor(s2, o);
-        }
-        if (sub == 0) {
-          const uint32_t cid0 = (uint32_t)((a * tb.Mmax + m) * B);
-          if (n1 > 0) {
-            const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
-            best = pk > best ? pk : best;
-          }
-          if (n2 > 0) {
-            const unsigned long long pk = pack_candidate(s2, cid0 + (uint32_t)(b2 - 1));
-            best = pk > best ? pk : best;
-          }
-        }
-      }
-    }
+    if (nbe > 0) best = triangle_best(kind, ent, lat_s, nbe, B, t, (uint32_t)((a * tb.Mmax + m) * B), nullptr);
     best = block_max_u64(best, red);
 
     // ---- publish this pair's best candidate ----
@@ -363,6 +323,10 @@ __global__ __launch_bounds__(kRoundThreads) void k_rounds_persistent(Tables tb, 
       st_dev(slot + 1, ((unsigned long long)__float_as_uint(lat_s[b - 1]) << 32) | (unsigned long long)gen);
       st_dev(slot, slot_word0(__uint_as_float((uint32_t)(best >> 32)), gen, valid, b));
     }
+
+    // ---- look-ahead: one step of the walk while the candidates are exchanged ----
+    // (three dependent trips to memory, about twice the exchange: only once less than two windows are left)
+    if (nb < min(2 * B, cap) && scan_end < seg_e) walk(1, 4);
 
     // ---- wait for the decision ----
     if (tid == 0) {
