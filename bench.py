@@ -173,7 +173,7 @@ def main():
                                f"N={n}, d={int(p.feat_dim)}, H={int(p.hidden_dim)}, seed {w.seed}; "
                                f"one scoring pass + {'greedy rounds until exhausted' if rounds <= 0 else str(rounds) + ' greedy rounds'}",
                    "n_requests": n, "rounds_run": n_rounds,
-                   "rounds_path": "one cooperative launch" if ctx.rounds_in_one_launch else "two kernels per round"},
+                   "rounds_path": "one launch" if ctx.rounds_in_one_launch else "two kernels per round"},
         "greedy_round_latency_us": {"mean": float(np.mean(per_round)) if per_round else None,
                                     "p50": float(np.percentile(per_round, 50)) if per_round else None,
                                     "p99": float(np.percentile(per_round, 99)) if per_round else None,

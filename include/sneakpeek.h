@@ -203,7 +203,7 @@ const char* sp_last_hip_error(const sp_ctx* ctx);
 int32_t sp_max_models(const sp_ctx* ctx);
 int32_t sp_max_classes(const sp_ctx* ctx);
 /* How sp_schedule runs the greedy rounds (Alg. 1, Sec. 5.1.1) on this context: 1 = all rounds of a chunk in
- * one cooperative launch (every (application, variant) pair fits on the device at once), 0 = two kernels
+ * one launch (every (application, variant) pair fits on the device at once), 0 = two kernels
  * per round.  The decisions are the same either way.  sp_greedy_round always takes the second way. */
 int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 

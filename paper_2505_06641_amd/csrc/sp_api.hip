@@ -50,7 +50,7 @@ struct sp_ctx {
   bool mlp_bf16 = false;             // bf16 MLP heads run on the matrix-core MLP kernel
   unsigned char* w1p = nullptr;      // packed layer-1 slices for that kernel
   int64_t* w1_off = nullptr;         // [A] byte offsets
-  // all rounds of a chunk in one cooperative launch, when every (application, variant) pair fits on the device at once
+  // all rounds of a chunk in one launch, when every (application, variant) pair fits on the device at once
   bool persist = false;
   Persist ps{};
   uint32_t gen_base = 0;             // slot generations handed out so far
@@ -371,8 +371,7 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
   const size_t n_pairs = pa.size();
   const size_t ring = (size_t)kPersistRounds * A * c->B;
   if (n_pairs == 0 || n_pairs > 4096 || ring > ((size_t)32 << 20)) return SP_OK;
-  int coop = 0, cus = 0, per_cu = 0, rate_khz = 0;
-  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, c->device) != hipSuccess || !coop) return SP_OK;
+  int cus = 0, per_cu = 0, rate_khz = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) return SP_OK;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent, kRoundThreads, 0) != hipSuccess) {
     (void)hipGetLastError();
@@ -408,7 +407,8 @@ void fill_u64(hipStream_t s, unsigned long long* p, size_t n) {
   hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, (int64_t)n, 0ull);
 }
 
-// Up to kPersistRounds rounds in one cooperative launch.
+// Up to kPersistRounds rounds in one launch.  An ordinary launch: setup_persist has checked that the whole
+// grid fits on the device at once, and the kernel's waits are bounded.
 sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
   Persist& ps = c->ps;
   if (c->gen_base + (uint32_t)n_rounds + 2u >= kGenMask) {       // generation numbers about to wrap: start over
@@ -420,8 +420,7 @@ sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
   ps.n_rounds = n_rounds;
   ps.gen_base = c->gen_base;
   c->gen_base += (uint32_t)n_rounds;
-  void* args[] = {(void*)&c->tb, (void*)&c->w, (void*)&ps};
-  SP_HIP(c, hipLaunchCooperativeKernel((const void*)k_rounds_persistent, dim3(ps.n_pairs + 2), dim3(kRoundThreads), args, 0, s));
+  hipLaunchKernelGGL(k_rounds_persistent, dim3(ps.n_pairs + 2), dim3(kRoundThreads), 0, s, c->tb, c->w, ps);
   return SP_OK;
 }
 
@@ -520,6 +519,7 @@ sp_status fetch_state(sp_ctx* c, hipStream_t s) {
     fill_u64(s, c->ps.dec, kPersistRounds);
     (void)hipStreamSynchronize(s);
     c->persist = false;
+    c->scored = false;                 // the window's state is not trustworthy any more: score it again
     return SP_EDEVICE;
   }
   return c->h_state->err ? SP_EINVAL : SP_OK;

@@ -23,8 +23,10 @@
 //   * the commit workgroup receives each decision through a ring entry, and the members of the chosen
 //     batch through a ring of generation-tagged window positions written by the chosen application's
 //     first pair, so the commits (outputs, totals, decision log) run beside the next round's scoring.
-// All waits are bounded: a wait that runs out raises kErrSync and every workgroup leaves its loop.
-// The launch must be cooperative (all workgroups resident at once).
+// The workgroups wait for each other, so all of them must be resident at once: the host launches this
+// kernel only when the device can hold the whole grid (occupancy query), and every wait is bounded: a
+// wait that runs out (the device was shared with other long-running work) raises kErrSync, every
+// workgroup leaves its loop, and the call fails instead of hanging.
 #pragma once
 #include "sp_rounds.h"
 
