@@ -197,6 +197,7 @@ sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
 sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p);
 sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p);
 sp_status setup_persist(sp_ctx* c, const sp_profile* p);
+int score_tile(const sp_ctx* c);
 
 sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   const int A = p->n_apps, B = p->max_batch;
@@ -256,6 +257,7 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &w.seg, A + 2)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.tile_start, A + 1)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.unit_start, A + 1)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.tile_desc, (size_t)c->cap / score_tile(c) + A + 1)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.ea, N * Mmax)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.key, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.D_s, N + 16)) != SP_OK) return s;      // +16: the window scan reads whole 16-groups
@@ -604,7 +606,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     }
   }
   hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, score_tile(c), unit, w.seg,
-                     w.tile_start, w.unit_start, w.head);
+                     w.tile_start, w.unit_start, w.head, w.tile_desc);
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;

@@ -62,6 +62,7 @@ struct Window {
   int32_t n;
   int32_t* seg;               // [A+2] start of each app's range in service order; seg[A] = #valid, seg[A+1] = n
   int32_t* tile_start;        // [A+1] prefix of scoring tiles
+  int4* tile_desc;            // per scoring tile: (application, first position, end of the application's range, 0)
   int32_t* unit_start;        // [A+1] prefix of sort units
   float* ea;                  // [n, Mmax]
   float* key;                 // [n]

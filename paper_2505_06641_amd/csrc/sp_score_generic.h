@@ -81,9 +81,9 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tile = blockIdx.x;
   if (tile >= w.tile_start[tb.A]) return;
-  const int a = find_segment(w.tile_start, tb.A, tile);
-  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
-  const int p0 = seg_b + (tile - w.tile_start[a]) * kScoreTile + wave * RW;   // first service position of this wave
+  const int4 desc = w.tile_desc[tile];
+  const int a = desc.x, seg_e = desc.z;
+  const int p0 = desc.y + wave * RW;                                           // first service position of this wave
   const int nr = min(RW, seg_e - p0);                                          // may be <= 0
   const int d = tb.d, H = tb.H, C = tb.n_classes[a], M = tb.n_models[a];
   float* xs = lds + (size_t)wave * RW * (d + H);

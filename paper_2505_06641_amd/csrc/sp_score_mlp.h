@@ -60,9 +60,9 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
   const int r = lane & 31, g = lane >> 5;
   const int tile = blockIdx.x;
   if (tile >= w.tile_start[tb.A]) return;
-  const int a = find_segment(w.tile_start, tb.A, tile);
-  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
-  const int pos = seg_b + (tile - w.tile_start[a]) * kMfTile + wave * 32 + r;
+  const int4 desc = w.tile_desc[tile];
+  const int a = desc.x, seg_e = desc.z;
+  const int pos = desc.y + wave * 32 + r;
   const bool valid = pos < seg_e;
   const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
   const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];

@@ -226,12 +226,16 @@ __device__ __forceinline__ void logits_phase(const float4* blk, const f16x8 (&xh
       wbuf[s % kPre][1] = wp[((s + kPre) * 2 + 1) * 64];
     }
     __builtin_amdgcn_sched_barrier(0);   // keep the reads of step s + kPre ahead of the MFMAs of step s
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
-    acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc2, 0, 0, 0);
-    if (s & 1)
+    // strict alternation between the two chains, also across k-steps (three MFMAs per step)
+    if (s & 1) {
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc2, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc, 0, 0, 0);
       acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc2, 0, 0, 0);
-    else
+    } else {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xh[s], acc, 0, 0, 0);
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(wl, xh[s], acc2, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wh, xl[s], acc, 0, 0, 0);
+    }
     __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
@@ -424,9 +428,9 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   const int r = lane & 31, g = lane >> 5;
   const int tile = blockIdx.x;
   if (tile >= w.tile_start[tb.A]) return;
-  const int a = find_segment(w.tile_start, tb.A, tile);
-  const int seg_b = w.seg[a], seg_e = w.seg[a + 1];
-  const int pos = seg_b + (tile - w.tile_start[a]) * kMfTile + wave * 32 + r;
+  const int4 desc = w.tile_desc[tile];
+  const int a = desc.x, seg_e = desc.z;
+  const int pos = desc.y + wave * 32 + r;
   const bool valid = pos < seg_e;
   const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
   const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];

@@ -171,10 +171,10 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
 
 // Segment starts from the application-sorted keys (values in [0, A], A =
 // invalid): seg[a] = first position with key >= a; then the prefixes of
-// scoring tiles and sort units per application.  One workgroup.
+// scoring tiles and sort units per application and the scoring tiles' descriptors.  One workgroup.
 __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
                                                   int tile, int unit, int32_t* seg, int32_t* tile_start,
-                                                  int32_t* unit_start, int32_t* head) {
+                                                  int32_t* unit_start, int32_t* head, int4* tile_desc) {
   for (int a = threadIdx.x; a <= A + 1; a += blockDim.x) {
     int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
     while (lo < hi) {
@@ -199,6 +199,19 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
     }
     tile_start[A] = ts;
     unit_start[A] = us;
+  }
+  __syncthreads();
+  // one descriptor per scoring tile, so that a scoring workgroup finds its place with a single load
+  if (A <= (int)blockDim.x) {
+    for (int a = 0; a < A; ++a) {
+      const int t0 = tile_start[a], nt = tile_start[a + 1] - t0, sb = seg[a], se = seg[a + 1];
+      for (int t = threadIdx.x; t < nt; t += blockDim.x) tile_desc[t0 + t] = make_int4(a, sb + t * tile, se, 0);
+    }
+  } else {
+    for (int a = threadIdx.x; a < A; a += blockDim.x) {
+      const int t0 = tile_start[a], nt = tile_start[a + 1] - t0, sb = seg[a], se = seg[a + 1];
+      for (int t = 0; t < nt; ++t) tile_desc[t0 + t] = make_int4(a, sb + t * tile, se, 0);
+    }
   }
 }
 
