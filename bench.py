@@ -29,6 +29,34 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_MFMA_F16_TFLOPS = 2500.0
 PEAK_VALU_F32_TFLOPS = 157.3
 
+# HBM traffic of the scoring kernel per launch, from hardware counters (rocprofv3 --pmc FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for the 256 MiB copy of --calibrate-copy; the
+# summaries are under profiles/).  A figure is only reported while the kernel sources it was taken on
+# are unchanged (sha256 over the files below).
+KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
+MEASURED_TRAFFIC = {
+    # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
+}
+
+
+def kernel_sources_sha():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2505_06641_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    ent = MEASURED_TRAFFIC.get(workload)
+    if ent is None:
+        return None
+    try:
+        return ent[0] if kernel_sources_sha() == ent[1] else None
+    except OSError:
+        return None
+
 
 def scoring_flops_per_request(p, a):
     """Algorithmic flops of the head and the EA contraction for one request of application a."""
@@ -161,7 +189,7 @@ def main():
         roof = {"bound": "mfma" if (split or mlp_mfma) else "alu", "achieved": tflops, "peak": peak_c, "unit": "TFLOP/s", "frac": tflops / peak_c}
     else:
         roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
-    roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": None,
+    roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": measured_traffic(args.workload),
                  "peak_note": peak_note, "x_fp32_mfma_peak": tflops / PEAK_MFMA_F32_TFLOPS,
                  "algorithmic_flops": flops, "algorithmic_bytes": k_bytes, "hbm_gbs": gbs, "tflops": tflops})
 
