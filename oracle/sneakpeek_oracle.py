@@ -21,6 +21,8 @@ What each function follows:
 * Window.*                 -- Alg. 1 generalised to batch-capped greedy rounds;
   eq. (1) clock with the batch as the unit; eq. (13) arg max.
 * dirichlet_posterior_mean -- Sec. 4.2, eq. (10)-(11).
+* smoothed_posterior       -- Sec. 4.2, eq. (10)-(11) with the head's output as
+  soft evidence (y = k * theta) under a per-application prior.
 
 Readings of points the paper leaves open (all listed in the design notes):
 the linear and sigmoid penalties are capped with min(1, .) (the printed
@@ -107,6 +109,17 @@ def dirichlet_posterior_mean(alpha, y):
     return p / p.sum()
 
 
+def smoothed_posterior(theta, alpha, k):
+    """Sec. 4.2: prior Dirichlet(alpha) (eq. 10), evidence a multinomial
+    observation of k draws; here the head's softmax output stands for the
+    neighbours' votes, y = k * theta, and the estimate is the mean of the
+    posterior Dirichlet(alpha + y) (eq. 11), row by row."""
+    theta = np.asarray(theta, dtype=np.float64)
+    alpha = widen(alpha)
+    rows = [dirichlet_posterior_mean(alpha, float(k) * theta[i]) for i in range(theta.shape[0])]
+    return np.asarray(rows, dtype=np.float64).reshape(theta.shape)
+
+
 # --------------------------------------------------------------------------
 # priority, penalty, utility (Sec. 3.1, 5.1, 6.1)
 # --------------------------------------------------------------------------
@@ -181,6 +194,9 @@ def score_requests(profile, requests, chunk=16384, return_theta=False):
             ids = sel[s:s + chunk]
             z = head_logits(requests.x[ids], profile.W1[a], profile.b1[a], profile.W2[a], profile.b2[a])
             th = posterior(z)
+            alpha = None if getattr(profile, "prior_alpha", None) is None else profile.prior_alpha[a]
+            if alpha is not None:
+                th = smoothed_posterior(th, alpha, profile.evidence_k[a])
             e = expected_accuracy(th, profile.acc[a])
             ea[ids, :M] = e
             key[ids] = request_priority(e, requests.deadline_rel_ms[ids], requests.weight[ids],

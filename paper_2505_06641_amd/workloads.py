@@ -50,6 +50,10 @@ class Profile:
     penalty: np.ndarray             # int32 [A]
     prio_timescale_ms: float = 1000.0
     max_requests: int = 0
+    # optional Dirichlet prior per application (Sec. 4.2): alpha float32 [C_a] or None, and the weight k
+    # (number of multinomial draws) the head's output carries as evidence
+    prior_alpha: Optional[List[Optional[np.ndarray]]] = None
+    evidence_k: Optional[np.ndarray] = None   # float32 [A]
 
 
 @dataclass
@@ -254,3 +258,28 @@ def tiny(seed: int, n: int, classes=(3,), models=(2,), max_batch=4, feat_dim=4, 
                  feat_dtype, max_batch, "he", ("uniform", 0.3, 0.99), ("uniform",) + tuple(alpha),
                  ("uniform",) + tuple(beta), tuple(deadline), "uniform", 0.0, 0, penalty)
     return generate(rec)
+
+
+def attach_priors(profile: Profile, seed: int, kinds=("jeffreys", "weak", "strong", None), window: int = 24) -> Profile:
+    """Gives every application a prior of the kinds Sec. 6.4 compares, cycling through `kinds`:
+    "jeffreys" alpha_c = 0.5; "weak" alpha = an expected label frequency vector; "strong" alpha =
+    expected label counts in a scheduling window of `window` requests; None = no prior.  The evidence
+    weight k is drawn from {1, 5, 10, 20}.  Seeded; holds no arithmetic of the method."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    alphas, ks = [], np.zeros(profile.n_apps, dtype=np.float32)
+    for a in range(profile.n_apps):
+        C = int(profile.n_classes[a])
+        kind = kinds[a % len(kinds)]
+        freq = rng.dirichlet(np.full(C, 0.7))
+        ks[a] = np.float32(rng.choice([1.0, 5.0, 10.0, 20.0]))
+        if kind is None:
+            alphas.append(None)
+        elif kind == "jeffreys":
+            alphas.append(np.full(C, 0.5, dtype=np.float32))
+        elif kind == "weak":
+            alphas.append(freq.astype(np.float32))
+        else:
+            alphas.append((freq * window).astype(np.float32))
+    profile.prior_alpha = alphas
+    profile.evidence_k = ks
+    return profile

@@ -197,6 +197,75 @@ def test_dirichlet_posterior_mean_of_the_papers_example(golden):
     assert got == pytest.approx([2.5 / 6.0, 3.5 / 6.0], rel=1e-15)
 
 
+def test_smoothed_posterior_reproduces_the_papers_example_from_vote_shares(golden):
+    # Sec. 4.2 "Evidence": five neighbours voting <2, 3> are the soft evidence 5 * (0.4, 0.6)
+    y = np.asarray(golden["knn_evidence_example"], dtype=np.float64)
+    a = golden["jeffreys_alpha"][0]
+    got = orc.smoothed_posterior((y / y.sum())[None, :], [a, a], y.sum())
+    assert got[0] == pytest.approx([2.5 / 6.0, 3.5 / 6.0], rel=1e-15)
+
+
+def test_smoothed_posterior_limits_and_shrinkage_form():
+    from fractions import Fraction
+    rng = np.random.default_rng(21)
+    C = 7
+    theta = rng.dirichlet(np.full(C, 0.4), size=5)
+    alpha = rng.uniform(0.1, 3.0, C)
+    # no evidence -> the prior mean, whatever the head says
+    got0 = orc.smoothed_posterior(theta, alpha, 0.0)
+    assert np.allclose(got0, np.tile(alpha / alpha.sum(), (5, 1)), rtol=1e-15, atol=0)
+    # overwhelming evidence -> the head's output; zero prior mass -> the head's output exactly
+    assert np.allclose(orc.smoothed_posterior(theta, alpha, 1e14), theta, rtol=0, atol=1e-12)
+    assert np.allclose(orc.smoothed_posterior(theta, np.zeros(C), 3.0), theta, rtol=1e-15, atol=0)
+    # textbook shrinkage form of a Dirichlet-multinomial posterior mean: lambda * theta + (1 - lambda) * prior mean
+    for k in (1.0, 5.0, 20.0):
+        lam = k / (alpha.sum() + k)
+        want = lam * theta + (1 - lam) * alpha / alpha.sum()
+        got = orc.smoothed_posterior(theta, alpha, k)
+        assert np.allclose(got, want, rtol=1e-13, atol=0)
+        assert np.allclose(got.sum(axis=1), 1.0, rtol=1e-14)
+    # exact rational arithmetic on a small case
+    th = [Fraction(1, 4), Fraction(1, 2), Fraction(1, 4)]
+    al = [Fraction(1, 2), Fraction(3, 2), Fraction(2)]
+    k = Fraction(10)
+    want = [(al[c] + k * th[c]) / (sum(al) + k) for c in range(3)]
+    got = orc.smoothed_posterior(np.array([[float(v) for v in th]]), [float(v) for v in al], float(k))
+    assert got[0] == pytest.approx([float(v) for v in want], rel=1e-15)
+
+
+def test_scoring_with_priors_uses_the_smoothed_posterior_everywhere():
+    w = wl.tiny(5, 40, classes=(3, 5, 2), models=(2, 3, 1))
+    wl.attach_priors(w.profile, seed=6, kinds=("weak", None, "strong"))
+    p, rq = w.profile, w.requests
+    ea, key, thetas = orc.score_requests(p, rq, return_theta=True)
+    w0 = wl.tiny(5, 40, classes=(3, 5, 2), models=(2, 3, 1))
+    ea0, key0, thetas0 = orc.score_requests(w0.profile, w0.requests, return_theta=True)
+    for i in range(rq.app.shape[0]):
+        a = int(rq.app[i]); M = int(p.n_models[a])
+        if p.prior_alpha[a] is None:
+            assert np.array_equal(thetas[i], thetas0[i]) and np.array_equal(ea[i], ea0[i]) and key[i] == key0[i]
+            continue
+        al = p.prior_alpha[a].astype(np.float64); k = float(p.evidence_k[a])
+        th = (al + k * thetas0[i]) / (al.sum() + k)
+        assert np.allclose(thetas[i], th, rtol=1e-14)
+        # eq. (9) on the smoothed posterior, and eq. (12) on those accuracies
+        want = [math.fsum(float(th[c]) * float(p.acc[a][m, c]) for c in range(len(th))) for m in range(M)]
+        assert ea[i, :M] == pytest.approx(want, rel=1e-13)
+        mu = sum(want) / M
+        var = sum((v - mu) ** 2 for v in want) / M
+        assert key[i] == pytest.approx(float(rq.weight[i]) * (1 + var) * math.exp(-float(rq.deadline_rel_ms[i]) / p.prio_timescale_ms), rel=1e-13)
+    # fallback of Sec. 4.1: with no evidence the estimate is the profiled accuracy under the prior's label mix
+    for a in range(p.n_apps):
+        p.evidence_k[a] = 0.0
+    ea_k0, _ = orc.score_requests(p, rq)
+    for i in range(rq.app.shape[0]):
+        a = int(rq.app[i]); M = int(p.n_models[a])
+        if p.prior_alpha[a] is None:
+            continue
+        mix = p.prior_alpha[a].astype(np.float64); mix = mix / mix.sum()
+        assert ea_k0[i, :M] == pytest.approx(orc.expected_accuracy(mix[None, :], p.acc[a])[0], rel=1e-13)
+
+
 def test_service_order_matches_python_sort_with_ties():
     rng = np.random.default_rng(9)
     n, A = 200, 3
