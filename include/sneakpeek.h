@@ -196,6 +196,19 @@ sp_status sp_set_timing(sp_ctx* ctx, int32_t enable);
 sp_status sp_get_timing(sp_ctx* ctx, sp_timing* out_host);
 sp_status sp_get_round_times(sp_ctx* ctx, float* ms_out_host, int32_t capacity, int32_t* n_out);
 
+/*
+ * Dirichlet prior of one application (Sec. 4.2, eq. (10)-(11); the kinds of prior: Sec. 6.3 "Choice of
+ * Prior").  alpha_host: HOST pointer to C_a values alpha_c >= 0 (copied), or NULL to remove the prior.
+ * evidence_k >= 0: the number of multinomial draws the head's output theta stands for (the paper's k
+ * neighbours; the evidence is y = k * theta).  From the next sp_score on, the posterior of that
+ * application's requests is the mean of Dirichlet(alpha + y), theta' = (alpha + k theta) / (sum alpha + k),
+ * and expected accuracies, keys and utilities follow from theta'.  The library folds this into an affine
+ * map of the expected accuracies, EA' = (sum_c alpha_c Acc[m][c] + k EA[m]) / (sum alpha + k), which is
+ * eq. (9) applied to theta'.  Synchronises the device.  SP_EINVAL: app out of range, a negative or
+ * non-finite alpha_c or k, sum alpha + k == 0.
+ */
+sp_status sp_set_prior(sp_ctx* ctx, int32_t app, const float* alpha_host, float evidence_k);
+
 const char* sp_strerror(sp_status s);
 /* Text of the last HIP error seen by this context (empty string if none). */
 const char* sp_last_hip_error(const sp_ctx* ctx);

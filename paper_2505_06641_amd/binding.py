@@ -21,7 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch",
+           "sp_rounds_in_one_launch", "sp_set_prior",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -98,6 +98,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_max_models.restype = C.c_int32
     lib.sp_max_classes.argtypes = [vp]
     lib.sp_max_classes.restype = C.c_int32
+    lib.sp_set_prior.argtypes = [vp, C.c_int32, C.c_void_p, C.c_float]
+    lib.sp_set_prior.restype = C.c_int
     lib.sp_rounds_in_one_launch.argtypes = [vp]
     lib.sp_rounds_in_one_launch.restype = C.c_int32
     lib.sp_set_timing.argtypes = [vp, C.c_int32]
@@ -193,6 +195,10 @@ class Context:
         self.c_max = self.lib.sp_max_classes(h)
         self.rounds_in_one_launch = bool(self.lib.sp_rounds_in_one_launch(h))
         self.n = 0
+        if getattr(profile, "prior_alpha", None) is not None:
+            for a in range(int(profile.n_apps)):
+                if profile.prior_alpha[a] is not None:
+                    self.sp_set_prior(a, profile.prior_alpha[a], float(profile.evidence_k[a]))
 
     def _check(self, rc, where, ok=(SP_OK,)):
         if rc not in ok:
@@ -236,6 +242,14 @@ class Context:
         self._check(rc, "sp_schedule", ok=(SP_OK, SP_DONE))
         n_log = min(sm.n_rounds, log_capacity)
         return rc, sm.as_dict(), [log[i].as_dict() for i in range(n_log)]
+
+    def sp_set_prior(self, app, alpha, evidence_k):
+        """alpha: host array of C_a floats, or None to remove the application's prior."""
+        if alpha is None:
+            return self._check(self.lib.sp_set_prior(self.h, int(app), None, C.c_float(0.0)), "sp_set_prior")
+        buf = np.ascontiguousarray(alpha, dtype=np.float32)
+        return self._check(self.lib.sp_set_prior(self.h, int(app), buf.ctypes.data_as(C.c_void_p),
+                                                 C.c_float(float(evidence_k))), "sp_set_prior")
 
     def sp_set_timing(self, level=1):
         """0 off, 1 stage events, 2 stage events and one event per round."""

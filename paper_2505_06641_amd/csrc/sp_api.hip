@@ -57,6 +57,11 @@ struct sp_ctx {
   long long* h_ticks = nullptr;      // pinned mirror of ps.ticks
   double tick_ms = 0.0;              // milliseconds per timestamp tick
   std::vector<float> round_ms;       // per-round latencies of the last timed sp_schedule on that path
+  // host copies needed to fold a prior into the expected accuracies (sp_set_prior)
+  std::vector<float> h_acc;
+  std::vector<int32_t> h_acc_off, h_ncls, h_nmod;
+  float* d_ea_gain = nullptr;
+  float* d_ea_bias = nullptr;
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -241,6 +246,14 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_upload(c, &d_lmin, lmin)) != SP_OK) return s;
   tb.n_classes = d_ncls; tb.n_models = d_nmod; tb.penalty = d_pen; tb.acc_off = d_acc_off;
   tb.acc = d_acc; tb.lat = d_lat; tb.lmin = d_lmin;
+  // no prior: gain 1, bias 0
+  c->h_acc = acc; c->h_acc_off = acc_off; c->h_ncls = ncls; c->h_nmod = nmod;
+  {
+    std::vector<float> gain((size_t)A, 1.0f), bias((size_t)A * Mmax, 0.0f);
+    if ((s = dev_upload(c, &c->d_ea_gain, gain)) != SP_OK) return s;
+    if ((s = dev_upload(c, &c->d_ea_bias, bias)) != SP_OK) return s;
+    tb.ea_gain = c->d_ea_gain; tb.ea_bias = c->d_ea_bias;
+  }
   s = (c->dtype == SP_BF16) ? upload_heads<uint16_t>(c, p) : upload_heads<float>(c, p);
   if (s != SP_OK) return s;
   if (c->H == 0 && c->dtype == SP_F32 && c->d <= 256) {
@@ -832,6 +845,38 @@ const char* sp_strerror(sp_status s) {
 }
 
 const char* sp_last_hip_error(const sp_ctx* c) { return c ? c->hip_err.c_str() : ""; }
+sp_status sp_set_prior(sp_ctx* c, int32_t app, const float* alpha_host, float evidence_k) {
+  if (!c || app < 0 || app >= c->A) return SP_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  const int C = c->h_ncls[app], M = c->h_nmod[app];
+  float gain = 1.0f;
+  std::vector<float> bias((size_t)c->Mmax, 0.0f);
+  if (alpha_host) {
+    if (!(evidence_k >= 0.f) || !std::isfinite(evidence_k)) return SP_EINVAL;
+    double sum = 0.0;
+    for (int cl = 0; cl < C; ++cl) {
+      if (!(alpha_host[cl] >= 0.f) || !std::isfinite(alpha_host[cl])) return SP_EINVAL;
+      sum += (double)alpha_host[cl];
+    }
+    const double den = sum + (double)evidence_k;
+    if (!(den > 0.0)) return SP_EINVAL;
+    // EA'[m] = (sum_c alpha_c Acc[m][c] + k EA[m]) / (sum alpha + k)
+    gain = (float)((double)evidence_k / den);
+    const float* acc = c->h_acc.data() + c->h_acc_off[app];
+    for (int m = 0; m < M; ++m) {
+      double t = 0.0;
+      for (int cl = 0; cl < C; ++cl) t += (double)alpha_host[cl] * (double)acc[(size_t)m * C + cl];
+      bias[m] = (float)(t / den);
+    }
+  }
+  // ordered after whatever the device is still doing with the old values
+  SP_HIP(c, hipDeviceSynchronize());
+  SP_HIP(c, hipMemcpy(c->d_ea_gain + app, &gain, sizeof(float), hipMemcpyHostToDevice));
+  SP_HIP(c, hipMemcpy(c->d_ea_bias + (size_t)app * c->Mmax, bias.data(), bias.size() * sizeof(float), hipMemcpyHostToDevice));
+  return SP_OK;
+}
+
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
 int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist) ? 1 : 0; }

@@ -34,6 +34,10 @@ struct Tables {
   const int32_t* acc_off;     // [A]
   const float* lat;           // [A, Mmax, B]
   const float* lmin;          // [A] min_m L[a][m][1]
+  // Dirichlet prior of Sec. 4.2 folded into an affine map of the expected accuracies:
+  // EA' = ea_gain[a] * EA + ea_bias[a][m]   (1 and 0 without a prior)
+  const float* ea_gain;       // [A]
+  const float* ea_bias;       // [A, Mmax]
 };
 
 struct Decision {             // mirrors sp_decision

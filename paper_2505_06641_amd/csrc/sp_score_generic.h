@@ -39,9 +39,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 // EA row -> population variance -> key; also the order-preserving sort key.
 // Called by one lane per request.
 template <int MT>
-__device__ __forceinline__ void finish_request(const Tables& tb, const Window& w, int pos, int id, int M,
-                                               const float (&ea)[MT], const float* D, const float* wt,
+__device__ __forceinline__ void finish_request(const Tables& tb, const Window& w, int a, int pos, int id, int M,
+                                               const float (&ea_raw)[MT], const float* D, const float* wt,
                                                uint32_t* sortkey) {
+  // with a prior (Sec. 4.2 eq. (10)-(11)) the posterior is (alpha + k theta) / (sum alpha + k), and
+  // eq. (9) on it is an affine map of eq. (9) on theta; gain 1 and bias 0 leave the value untouched
+  float ea[MT];
+  const float gain = tb.ea_gain[a];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) ea[m] = (m < M) ? fmaf(gain, ea_raw[m], tb.ea_bias[a * tb.Mmax + m]) : 0.f;
   float mean = 0.f;
 #pragma unroll
   for (int m = 0; m < MT; ++m) mean += (m < M) ? ea[m] : 0.f;
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
     float row[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) row[m] = wave_sum(ea[r][m] * f) / st;
-    if (lane == 0 && r < nr && logits_out == nullptr) finish_request<MT>(tb, w, p0 + r, ids[p0 + r], M, row, D, wt, sortkey);
+    if (lane == 0 && r < nr && logits_out == nullptr) finish_request<MT>(tb, w, a, p0 + r, ids[p0 + r], M, row, D, wt, sortkey);
   }
 }
 

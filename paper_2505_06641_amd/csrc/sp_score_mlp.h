@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     }
   }
 
-  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
                                   sortkey, logits_out);
 }
 

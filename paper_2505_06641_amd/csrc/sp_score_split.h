@@ -314,7 +314,7 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
 template <int D, bool DUMP>
 __device__ __forceinline__ void class_tiles_and_finish(
     const Tables& tb, const Window& w, float4* buf_a, float4* buf_b, float4* buf_c, const float4* __restrict__ src,
-    const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale, int CT, int C, int M, int pos, int id,
+    const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale, int a, int CT, int C, int M, int pos, int id,
     bool valid, const float* __restrict__ Dl, const float* __restrict__ wt, uint32_t* __restrict__ sortkey,
     float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
@@ -374,12 +374,15 @@ __device__ __forceinline__ void class_tiles_and_finish(
   // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
   const float ssum = __shfl(eacc[8], r);
   const float inv = 1.0f / ssum;
+  // prior of Sec. 4.2 eq. (10)-(11) as an affine map of the expected accuracies (gain 1, bias 0 without one)
+  const float gain = tb.ea_gain[a];
+  const float* biasp = tb.ea_bias + a * tb.Mmax;
   float ea[8];
   float part = 0.f;
 #pragma unroll
   for (int v = 0; v < 8; ++v) {
     const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    ea[v] = (m < M) ? eacc[v] * inv : 0.f;
+    ea[v] = (m < M) ? fmaf(gain, eacc[v] * inv, biasp[m]) : 0.f;
     part += ea[v];
   }
   const float mean = (part + __shfl_xor(part, 32)) / (float)M;
@@ -510,7 +513,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       xl[q >> 3][q & 7] = lo;
     }
   }
-  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
                                   sortkey, logits_out);
 }
 

@@ -155,6 +155,51 @@ def test_bf16_ragged(gpu):
     full_parity(gpu, w, max_rounds=0, ea_tol=2e-3)
 
 
+@pytest.mark.parametrize("head", ["logistic", "mlp_f32", "mlp_bf16"])
+def test_dirichlet_priors_on_every_scoring_kernel(gpu, head):
+    """Sec. 4.2 eq. (10)-(11): priors of the three kinds of Sec. 6.3 and one application without a prior."""
+    kw = dict(classes=(5, 12, 130, 2), models=(3, 1, 16, 7), max_batch=9, deadline=(4.0, 60.0), fractions=(0.4, 0.1, 0.3, 0.2))
+    if head == "logistic":
+        w = wl.tiny(seed=90, n=2500, feat_dim=19, hidden_dim=0, **kw)
+    elif head == "mlp_f32":
+        w = wl.tiny(seed=91, n=1200, feat_dim=33, hidden_dim=17, **kw)
+    else:
+        w = wl.tiny(seed=92, n=1500, feat_dim=24, hidden_dim=10, feat_dtype=wl.BF16, **kw)
+    wl.attach_priors(w.profile, seed=93)
+    plain, _ = orc.score_requests(wl.tiny(seed=w.seed, n=w.requests.app.shape[0], feat_dim=w.profile.feat_dim,
+                                          hidden_dim=w.profile.hidden_dim, feat_dtype=w.profile.feat_dtype, **kw).profile,
+                                  w.requests)
+    smooth, _ = orc.score_requests(w.profile, w.requests)
+    assert np.max(np.abs(plain - smooth)) > 1e-3          # the priors do move the estimates
+    full_parity(gpu, w, max_rounds=0, ea_tol=2e-3 if head == "mlp_bf16" else None, want_cube=head != "mlp_bf16")
+
+
+def test_prior_can_be_removed_and_bad_priors_are_rejected(gpu):
+    torch, binding = gpu
+    w = wl.tiny(seed=94, n=300, classes=(4, 6), models=(2, 3), max_batch=4, feat_dim=8)
+    ea_plain, _ = orc.score_requests(w.profile, w.requests)
+    ctx = binding.Context(w.profile, 300)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_set_prior(1, np.array([2.0, 0.5, 0.5, 1.0, 3.0, 0.25], dtype=np.float32), 5.0)
+    ea = torch.zeros((300, ctx.m_max), device="cuda:0")
+    ctx.sp_score(x, app, D, wt, ea_out=ea)
+    ea1 = ea.cpu().numpy()
+    ctx.sp_set_prior(1, None, 0.0)
+    ctx.sp_score(x, app, D, wt, ea_out=ea)
+    ea2 = ea.cpu().numpy()
+    assert np.max(np.abs(ea1 - ea_plain)) > 1e-3
+    parity.assert_close("EA", ea2, ea_plain, TOL)
+    for bad_alpha, k in (([1.0, -0.1, 1.0, 1.0], 1.0), ([1.0, float("nan"), 1.0, 1.0], 1.0), ([0.0] * 4, 0.0),
+                         ([1.0] * 4, -1.0)):
+        with pytest.raises(binding.SneakPeekError) as e:
+            ctx.sp_set_prior(0, np.asarray(bad_alpha, dtype=np.float32), k)
+        assert e.value.status == binding.SP_EINVAL
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_set_prior(2, np.ones(4, dtype=np.float32), 1.0)
+    assert e.value.status == binding.SP_EINVAL
+    ctx.close()
+
+
 def test_batch_of_one(gpu):
     w = wl.tiny(seed=52, n=200, classes=(4, 3), models=(3, 2), max_batch=1, feat_dim=8, deadline=(3.0, 40.0))
     got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True)
