@@ -33,7 +33,9 @@ strictly later; exp(-d) in eq. (12) takes the remaining time in units of a
 timescale T_d (1000 ms by default); the per-request weight w multiplies both
 the key and the reported utility (w = 1 recovers the paper); every member of a
 batch completes at t + L[m,b]; a request is dead once its penalty would be 1
-even alone on the fastest variant, and dead requests never come back.
+even alone on the fastest variant, and dead requests never come back; an
+optional swap-in cost per variant is paid by every batch whose variant differs
+from the previous batch's (liveness ignores it, so that it stays monotone).
 
 Parity status: every function here is pinned by tests/test_oracle_*.py
 against closed forms, the paper's worked numbers, or brute force, except the
@@ -238,6 +240,12 @@ class Window:
         self.order = service_order(self.app, self.key, profile.n_apps)
         self.lat = [widen(l) for l in profile.lat_ms]
         self.lmin = [float(l[:, 0].min()) for l in self.lat]
+        # cost of bringing a variant in (Sec. 3.1: latency "including any context switch time"; Sec. 5.2:
+        # grouping "avoids the additional latency associated with swapping models in and out"): paid by
+        # a batch unless the previous batch of the window ran the same variant of the same application
+        swap = getattr(profile, "swap_ms", None)
+        self.swap = [None if (swap is None or swap[a] is None) else widen(swap[a]) for a in range(int(profile.n_apps))]
+        self.resident = None                 # (application, variant) of the last committed batch
         self.alive = np.ones(self.n, dtype=bool)
         self.t = 0.0
         self.round = 0
@@ -260,6 +268,13 @@ class Window:
     def candidate_window(self, a):
         return self.live_queue(a)[: int(self.p.max_batch)]
 
+    def start_time(self, a, m):
+        """When a batch on variant m of application a starts computing: now, plus the swap-in cost
+        unless that variant is the resident one."""
+        if self.swap[a] is None or self.resident == (a, m):
+            return self.t
+        return self.t + self.swap[a][m]
+
     # -- candidate scores ----------------------------------------------------
     def score_cube(self):
         """Score[a, m, b-1] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
@@ -275,7 +290,7 @@ class Window:
             kind = int(self.p.penalty[a])
             for m in range(int(self.p.n_models[a])):
                 for b in range(1, nb + 1):
-                    e = self.t + self.lat[a][m, b - 1]
+                    e = self.start_time(a, m) + self.lat[a][m, b - 1]
                     members = q[:b]
                     terms = self.key[members] * utility(self.ea[members, m], kind, self.D[members], e)
                     cube[a, m, b - 1] = terms.sum()
@@ -296,7 +311,7 @@ class Window:
             kind = int(self.p.penalty[a])
             tri = np.tril(np.ones((nb, nb), dtype=bool))          # [b, j]: j <= b
             for m in range(int(self.p.n_models[a])):
-                e = self.t + self.lat[a][m, :nb]                   # [b]
+                e = self.start_time(a, m) + self.lat[a][m, :nb]    # [b]
                 u = utility(self.ea[q, m][None, :], kind, self.D[q][None, :], e[:, None])
                 terms = np.where(tri, self.key[q][None, :] * u, 0.0)
                 cube[a, m, :nb] = terms.sum(axis=1)
@@ -314,7 +329,8 @@ class Window:
         b = int(bi) + 1
         ids = self.candidate_window(int(a))[:b]
         return {"app": int(a), "model": int(m), "batch": b, "score": float(cube[a, m, bi]),
-                "ids": ids.copy(), "t_start": self.t, "t_end": self.t + self.lat[int(a)][int(m), bi]}
+                "ids": ids.copy(), "t_start": self.t,
+                "t_end": self.start_time(int(a), int(m)) + self.lat[int(a)][int(m), bi]}
 
     # -- commit ---------------------------------------------------------------
     def commit(self, a, m, ids):
@@ -323,7 +339,7 @@ class Window:
         b = int(ids.shape[0])
         assert 1 <= b <= int(self.p.max_batch)
         assert np.all(self.app[ids] == a) and np.all(self.alive[ids])
-        t_end = self.t + self.lat[a][m, b - 1]
+        t_end = self.start_time(a, m) + self.lat[a][m, b - 1]
         u = utility(self.ea[ids, m], int(self.p.penalty[a]), self.D[ids], t_end)
         self.model[ids] = m
         self.round_of[ids] = self.round
@@ -337,6 +353,7 @@ class Window:
         self.next_order += b
         self.round += 1
         self.t = t_end
+        self.resident = (a, m)
         return rec
 
     def step(self):

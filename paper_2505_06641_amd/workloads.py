@@ -54,6 +54,8 @@ class Profile:
     # (number of multinomial draws) the head's output carries as evidence
     prior_alpha: Optional[List[Optional[np.ndarray]]] = None
     evidence_k: Optional[np.ndarray] = None   # float32 [A]
+    # optional swap-in cost per variant (Sec. 3.1 "context switch time"): float32 [M_a] per app or None
+    swap_ms: Optional[List[Optional[np.ndarray]]] = None
 
 
 @dataclass
@@ -282,4 +284,15 @@ def attach_priors(profile: Profile, seed: int, kinds=("jeffreys", "weak", "stron
             alphas.append((freq * window).astype(np.float32))
     profile.prior_alpha = alphas
     profile.evidence_k = ks
+    return profile
+
+
+def attach_swap_costs(profile: Profile, seed: int, lo: float = 0.5, hi: float = 8.0, skip_every: int = 0) -> Profile:
+    """Uniform(lo, hi) ms of swap-in cost for every variant (every `skip_every`-th application gets none)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for a in range(profile.n_apps):
+        v = rng.uniform(lo, hi, int(profile.n_models[a])).astype(np.float32)
+        out.append(None if (skip_every and a % skip_every == skip_every - 1) else v)
+    profile.swap_ms = out
     return profile

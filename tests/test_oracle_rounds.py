@@ -280,3 +280,77 @@ def test_max_rounds_stops_early_and_resumes():
     part.run()
     assert [(r["app"], r["model"], r["batch"]) for r in part.log] == \
            [(r["app"], r["model"], r["batch"]) for r in full.log]
+
+
+# ---- swap-in cost of a variant (Sec. 3.1 "context switch time", Sec. 5.2 model locality) -----------
+def test_swap_cost_is_paid_once_per_run_of_batches_on_the_same_variant():
+    # one application, one variant, deadlines that nothing can miss: the greedy serves the queue in
+    # full batches back to back, so the clock ends at swap + sum of batch latencies
+    w = wl.tiny(seed=300, n=10, classes=(3,), models=(1,), max_batch=4, deadline=(1e3, 2e3))
+    w.profile.swap_ms = [np.array([7.5], dtype=np.float32)]
+    win = orc.Window(w.profile, w.requests)
+    win.run()
+    L = w.profile.lat_ms[0][0].astype(np.float64)
+    assert [r["batch"] for r in win.log] == [4, 4, 2]
+    assert win.t == pytest.approx(7.5 + L[3] + L[3] + L[1], rel=1e-15)
+    assert win.log[0]["t_end"] == pytest.approx(7.5 + L[3], rel=1e-15)
+    assert win.log[1]["t_end"] - win.log[1]["t_start"] == pytest.approx(L[3], rel=1e-12)
+
+
+@pytest.mark.parametrize("seed,kind", [(s, k) for s in range(4) for k in (STEP, LINEAR, SIGMOID)])
+def test_round_with_swap_costs_against_direct_enumeration(seed, kind):
+    w = wl.tiny(seed=310 + seed, n=9, classes=(3, 2), models=(3, 2), max_batch=3, penalty=kind, deadline=(4.0, 30.0))
+    wl.attach_swap_costs(w.profile, seed=320 + seed, lo=0.5, hi=6.0)
+    win = orc.Window(w.profile, w.requests)
+    resident = None
+    for _ in range(4):
+        best = None
+        for a in range(2):
+            ranked = sorted(live_ids(win, a), key=lambda i: (-win.key[i], i))
+            for m in range(int(w.profile.n_models[a])):
+                start = win.t + (0.0 if resident == (a, m) else float(w.profile.swap_ms[a][m]))
+                for b in range(1, min(3, len(ranked)) + 1):
+                    e = start + float(w.profile.lat_ms[a][m, b - 1])
+                    v = math.fsum(win.key[i] * win.ea[i, m] * (1.0 - gamma(kind, win.D[i], e)) for i in ranked[:b])
+                    if best is None or v > best[0]:
+                        best = (v, a, m, b, e)
+        d = win.decide()
+        if best is None:
+            assert d is None
+            break
+        assert (d["app"], d["model"], d["batch"]) == best[1:4]
+        assert d["score"] == pytest.approx(best[0], rel=1e-12)
+        assert d["t_end"] == pytest.approx(best[4], rel=1e-15)
+        win.commit(d["app"], d["model"], d["ids"])
+        resident = (d["app"], d["model"])
+        assert win.t == pytest.approx(best[4], rel=1e-15)
+
+
+def test_zero_or_missing_swap_costs_change_nothing():
+    w = wl.tiny(seed=330, n=40, classes=(3, 4), models=(2, 3), max_batch=5, deadline=(4.0, 60.0))
+    ref = orc.Window(w.profile, w.requests); ref.run()
+    w.profile.swap_ms = [np.zeros(2, dtype=np.float32), None]
+    got = orc.Window(w.profile, w.requests); got.run()
+    assert [(r["app"], r["model"], r["batch"], r["t_end"]) for r in got.log] == \
+           [(r["app"], r["model"], r["batch"], r["t_end"]) for r in ref.log]
+
+
+def test_swap_cost_makes_the_greedy_stay_on_the_resident_variant():
+    # two equally accurate variants, the second a shade faster but costly to bring in; every request is
+    # already late when it completes (linear penalty), so faster is strictly better: without swap cost
+    # the greedy takes the faster variant, with it the cheap-to-load one, and then stays on it
+    w = wl.tiny(seed=340, n=8, classes=(2,), models=(2,), max_batch=2, penalty=LINEAR, deadline=(20.0, 21.0))
+    p = w.profile
+    p.acc[0][:] = 0.9
+    p.lat_ms[0][0] = np.array([23.0, 24.0], dtype=np.float32)
+    p.lat_ms[0][1] = np.array([22.0, 23.0], dtype=np.float32)
+    plain = orc.Window(p, w.requests)
+    assert plain.step()["model"] == 1
+    p.swap_ms = [np.array([0.5, 6.0], dtype=np.float32)]
+    sw = orc.Window(p, w.requests)
+    first = sw.step()
+    assert first["model"] == 0 and first["t_end"] == pytest.approx(0.5 + float(p.lat_ms[0][0][first["batch"] - 1]))
+    second = sw.step()
+    if second is not None:
+        assert second["model"] == 0
+        assert second["t_end"] - second["t_start"] == pytest.approx(float(p.lat_ms[0][0][second["batch"] - 1]), rel=1e-12)
