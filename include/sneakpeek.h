@@ -209,6 +209,19 @@ sp_status sp_get_round_times(sp_ctx* ctx, float* ms_out_host, int32_t capacity, 
  */
 sp_status sp_set_prior(sp_ctx* ctx, int32_t app, const float* alpha_host, float evidence_k);
 
+/*
+ * Swap-in cost of the variants of one application (Sec. 3.1: a variant's latency "including any context
+ * switch time"; Sec. 5.2: grouping exploits model locality and avoids swapping models in and out).
+ * swap_ms_host: HOST pointer to M_a values >= 0 (copied), or NULL for none.  A batch on variant m of that
+ * application then completes at t + swap_ms[m] + L[a][m][b] unless the previous batch of the window ran
+ * the same variant of the same application, in which case it completes at t + L[a][m][b]; candidates are
+ * scored with the completion time they would really have.  The first batch of a window always pays.
+ * Liveness does not look at swap costs (a request is dead once t + min_m L[a][m][1] makes its penalty
+ * 1), so that dead requests stay dead.  Takes effect from the next round on.  Synchronises the
+ * device.  SP_EINVAL: app out of range, a negative or non-finite cost.
+ */
+sp_status sp_set_swap_cost(sp_ctx* ctx, int32_t app, const float* swap_ms_host);
+
 const char* sp_strerror(sp_status s);
 /* Text of the last HIP error seen by this context (empty string if none). */
 const char* sp_last_hip_error(const sp_ctx* ctx);

@@ -21,7 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch", "sp_set_prior",
+           "sp_rounds_in_one_launch", "sp_set_prior", "sp_set_swap_cost",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -100,6 +100,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_max_classes.restype = C.c_int32
     lib.sp_set_prior.argtypes = [vp, C.c_int32, C.c_void_p, C.c_float]
     lib.sp_set_prior.restype = C.c_int
+    lib.sp_set_swap_cost.argtypes = [vp, C.c_int32, C.c_void_p]
+    lib.sp_set_swap_cost.restype = C.c_int
     lib.sp_rounds_in_one_launch.argtypes = [vp]
     lib.sp_rounds_in_one_launch.restype = C.c_int32
     lib.sp_set_timing.argtypes = [vp, C.c_int32]
@@ -195,6 +197,10 @@ class Context:
         self.c_max = self.lib.sp_max_classes(h)
         self.rounds_in_one_launch = bool(self.lib.sp_rounds_in_one_launch(h))
         self.n = 0
+        if getattr(profile, "swap_ms", None) is not None:
+            for a in range(int(profile.n_apps)):
+                if profile.swap_ms[a] is not None:
+                    self.sp_set_swap_cost(a, profile.swap_ms[a])
         if getattr(profile, "prior_alpha", None) is not None:
             for a in range(int(profile.n_apps)):
                 if profile.prior_alpha[a] is not None:
@@ -250,6 +256,14 @@ class Context:
         buf = np.ascontiguousarray(alpha, dtype=np.float32)
         return self._check(self.lib.sp_set_prior(self.h, int(app), buf.ctypes.data_as(C.c_void_p),
                                                  C.c_float(float(evidence_k))), "sp_set_prior")
+
+    def sp_set_swap_cost(self, app, swap_ms):
+        """swap_ms: host array of M_a floats, or None for no swap-in cost."""
+        if swap_ms is None:
+            return self._check(self.lib.sp_set_swap_cost(self.h, int(app), None), "sp_set_swap_cost")
+        buf = np.ascontiguousarray(swap_ms, dtype=np.float32)
+        return self._check(self.lib.sp_set_swap_cost(self.h, int(app), buf.ctypes.data_as(C.c_void_p)),
+                           "sp_set_swap_cost")
 
     def sp_set_timing(self, level=1):
         """0 off, 1 stage events, 2 stage events and one event per round."""

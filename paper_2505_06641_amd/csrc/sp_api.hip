@@ -62,6 +62,7 @@ struct sp_ctx {
   std::vector<int32_t> h_acc_off, h_ncls, h_nmod;
   float* d_ea_gain = nullptr;
   float* d_ea_bias = nullptr;
+  float* d_swap = nullptr;
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -253,6 +254,8 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
     if ((s = dev_upload(c, &c->d_ea_gain, gain)) != SP_OK) return s;
     if ((s = dev_upload(c, &c->d_ea_bias, bias)) != SP_OK) return s;
     tb.ea_gain = c->d_ea_gain; tb.ea_bias = c->d_ea_bias;
+    if ((s = dev_upload(c, &c->d_swap, bias)) != SP_OK) return s;      // no swap-in costs
+    tb.swap = c->d_swap;
   }
   s = (c->dtype == SP_BF16) ? upload_heads<uint16_t>(c, p) : upload_heads<float>(c, p);
   if (s != SP_OK) return s;
@@ -402,13 +405,13 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_upload(c, &d_pa, pa)) != SP_OK) return s;
   if ((s = dev_upload(c, &d_pm, pm)) != SP_OK) return s;
   ps.pair_app = d_pa; ps.pair_model = d_pm; ps.n_pairs = (int32_t)n_pairs;
-  if ((s = dev_alloc(c, &ps.slots, 4 * n_pairs)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &ps.slots, 8 * n_pairs)) != SP_OK) return s;
   if ((s = dev_alloc(c, &ps.ring, ring)) != SP_OK) return s;
   if ((s = dev_alloc(c, &ps.dec, kPersistRounds)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &ps.decision, 4)) != SP_OK) return s;
-  SP_HIP(c, hipMemset(ps.decision, 0, 4 * 8));
+  if ((s = dev_alloc(c, &ps.decision, 8)) != SP_OK) return s;
+  SP_HIP(c, hipMemset(ps.decision, 0, 8 * 8));
   if ((s = dev_alloc(c, &ps.ticks, kPersistRounds + 1)) != SP_OK) return s;
-  SP_HIP(c, hipMemset(ps.slots, 0, 4 * n_pairs * 8));
+  SP_HIP(c, hipMemset(ps.slots, 0, 8 * n_pairs * 8));
   SP_HIP(c, hipMemset(ps.ring, 0, ring * 8));
   SP_HIP(c, hipMemset(ps.dec, 0, kPersistRounds * 8));
   SP_HIP(c, hipMemset(ps.ticks, 0, (kPersistRounds + 1) * 8));
@@ -427,8 +430,8 @@ void fill_u64(hipStream_t s, unsigned long long* p, size_t n) {
 sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
   Persist& ps = c->ps;
   if (c->gen_base + (uint32_t)n_rounds + 2u >= kGenMask) {       // generation numbers about to wrap: start over
-    fill_u64(s, ps.slots, 4 * (size_t)ps.n_pairs);
-    fill_u64(s, ps.decision, 4);
+    fill_u64(s, ps.slots, 8 * (size_t)ps.n_pairs);
+    fill_u64(s, ps.decision, 8);
     fill_u64(s, ps.ring, (size_t)kPersistRounds * c->A * c->B);
     c->gen_base = 0;
   }
@@ -530,7 +533,7 @@ sp_status fetch_state(sp_ctx* c, hipStream_t s) {
   if (c->h_state->err & kErrSync) {
     // resident workgroups lost each other: leave the exchange buffers clean and stop using that path
     c->hip_err = "rounds kernel: a wait between workgroups ran out";
-    fill_u64(s, c->ps.slots, 4 * (size_t)c->ps.n_pairs);
+    fill_u64(s, c->ps.slots, 8 * (size_t)c->ps.n_pairs);
     fill_u64(s, c->ps.dec, kPersistRounds);
     (void)hipStreamSynchronize(s);
     c->persist = false;
@@ -874,6 +877,22 @@ sp_status sp_set_prior(sp_ctx* c, int32_t app, const float* alpha_host, float ev
   SP_HIP(c, hipDeviceSynchronize());
   SP_HIP(c, hipMemcpy(c->d_ea_gain + app, &gain, sizeof(float), hipMemcpyHostToDevice));
   SP_HIP(c, hipMemcpy(c->d_ea_bias + (size_t)app * c->Mmax, bias.data(), bias.size() * sizeof(float), hipMemcpyHostToDevice));
+  return SP_OK;
+}
+
+sp_status sp_set_swap_cost(sp_ctx* c, int32_t app, const float* swap_ms_host) {
+  if (!c || app < 0 || app >= c->A) return SP_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  const int M = c->h_nmod[app];
+  std::vector<float> v((size_t)c->Mmax, 0.0f);
+  if (swap_ms_host)
+    for (int m = 0; m < M; ++m) {
+      if (!(swap_ms_host[m] >= 0.f) || !std::isfinite(swap_ms_host[m])) return SP_EINVAL;
+      v[m] = swap_ms_host[m];
+    }
+  SP_HIP(c, hipDeviceSynchronize());
+  SP_HIP(c, hipMemcpy(c->d_swap + (size_t)app * c->Mmax, v.data(), v.size() * sizeof(float), hipMemcpyHostToDevice));
   return SP_OK;
 }
 

@@ -36,6 +36,7 @@ struct Tables {
   const float* lmin;          // [A] min_m L[a][m][1]
   // Dirichlet prior of Sec. 4.2 folded into an affine map of the expected accuracies:
   // EA' = ea_gain[a] * EA + ea_bias[a][m]   (1 and 0 without a prior)
+  const float* swap;          // [A, Mmax] cost of bringing a variant in, paid unless the previous batch ran it
   const float* ea_gain;       // [A]
   const float* ea_bias;       // [A, Mmax]
 };

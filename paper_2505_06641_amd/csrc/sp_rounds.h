@@ -22,6 +22,13 @@ namespace sp {
 constexpr int kRoundThreads = 512;
 constexpr int kPairLanes = 8;                       // lanes that share one pair of batch sizes in the triangle
 
+// When a batch on variant m of application a starts computing: now, plus the variant's swap-in cost
+// unless the previous batch of the window ran the same variant (Sec. 3.1 "context switch time";
+// Sec. 5.2 model locality).  prev.app is -1 before the first batch.
+__device__ __forceinline__ double start_time(const Tables& tb, const Decision& prev, double t, int a, int m) {
+  return (prev.app == a && prev.model == m) ? t : t + (double)tb.swap[a * tb.Mmax + m];
+}
+
 __device__ __forceinline__ unsigned long long pack_candidate(float score, uint32_t cand_id) {
   return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - cand_id);
 }
@@ -201,7 +208,8 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   for (int j = tid; j < nb; j += kRoundThreads) ent[j] = window_entry(tb, w, win[j], m);
   __syncthreads();
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
-  unsigned long long best = triangle_best(kind, ent, lat, nb, B, t, (uint32_t)((a * tb.Mmax + m) * B), cube_out);
+  const double t0 = start_time(tb, st->last, t, a, m);
+  unsigned long long best = triangle_best(kind, ent, lat, nb, B, t0, (uint32_t)((a * tb.Mmax + m) * B), cube_out);
   best = block_max_u64(best, red);
   if (tid == 0) w.cand[blockIdx.x] = best;
 }
@@ -273,7 +281,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   const int r = st->round;
   const double t = st->t;
   const int next_order = st->next_order;
-  const double E = t + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
+  const double E = start_time(tb, st->last, t, a, m) + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
   double wu, su, viol;
   const int32_t* row = w.win_pos + a * B;
   commit_members(tb, w, a, m, b, r, next_order, E, [&](int j) { return row[j]; }, ids_out, dsum, wu, su, viol);
@@ -299,6 +307,7 @@ __global__ void k_reset_state(State* st) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     st->t = 0.0; st->total_wu = 0.0; st->total_u = 0.0; st->total_viol = 0.0;
     st->round = 0; st->next_order = 1; st->n_sched = 0; st->done = 0; st->err = 0u; st->pad = 0;
+    st->last.app = -1; st->last.model = -1;      // nothing resident yet
   }
 }
 

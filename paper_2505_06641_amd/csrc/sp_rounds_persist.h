@@ -44,8 +44,9 @@ struct Persist {
   int32_t n_pairs;
   int32_t n_rounds;             // rounds this launch may run (<= kPersistRounds)
   uint32_t gen_base;            // generations used by earlier launches
-  unsigned long long* slots;    // [2 (parity), n_pairs, 2 (word)]
-  unsigned long long* decision; // [2 (parity), 2 (word)]: latency bits << 32 | gen; (candidate id + 1, 0 = none) << 32 | gen
+  unsigned long long* slots;    // [2 (parity), n_pairs, 4 (word; the last one unused)]
+  unsigned long long* decision; // [2 (parity), 4 (word)]: latency bits << 32 | gen; (candidate id + 1, 0 = none)
+                                //   << 32 | gen; swap-in cost bits << 32 | gen; unused
   unsigned long long* ring;     // [kPersistRounds, A, B]: generation << 32 | service position
   unsigned long long* dec;      // [kPersistRounds]: decision of each round, bit 63 set; zero once consumed
   long long* ticks;             // [kPersistRounds + 1]: constant-rate timestamps, launch start then each decision
@@ -60,6 +61,7 @@ __device__ __forceinline__ void st_dev(unsigned long long* p, unsigned long long
 
 // slot word 0: score bits << 32 | generation (23 bits) << 9 | valid << 8 | (b - 1)
 // slot word 1: latency bits of the candidate (float) << 32 | generation (32 bits)
+// slot word 2: swap-in cost the pair would pay in this round (float bits) << 32 | generation (32 bits)
 __device__ __forceinline__ unsigned long long slot_word0(float score, uint32_t gen, bool valid, int b) {
   return ((unsigned long long)__float_as_uint(score) << 32) | ((unsigned long long)(gen & kGenMask) << 9) |
          (valid ? 0x100ull : 0ull) | (unsigned long long)((b - 1) & 0xff);
@@ -72,7 +74,7 @@ __device__ void persist_commit_loop(const Tables& tb, const Window& w, const Per
   int r = st->round, next_order = st->next_order, n_sched = st->n_sched;
   double t = st->t, twu = st->total_wu, tu = st->total_u, tv = st->total_viol;
   bool done = false, failed = false, any = false;
-  Decision last;
+  Decision last = st->last;                 // app -1 before the window's first batch
   for (int rl = 0; rl < ps.n_rounds; ++rl) {
     const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
     if (tid == 0) {
@@ -97,7 +99,7 @@ __device__ void persist_commit_loop(const Tables& tb, const Window& w, const Per
     const int b = (int)(cid % (uint32_t)B) + 1;
     const int am = (int)(cid / (uint32_t)B);
     const int m = am % tb.Mmax, a = am / tb.Mmax;
-    const double E = t + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
+    const double E = start_time(tb, last, t, a, m) + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
     const unsigned long long* row = ps.ring + ((size_t)rl * tb.A + a) * B;
     bool lost = false;
     double wu, su, viol;
@@ -132,7 +134,7 @@ __device__ void persist_commit_loop(const Tables& tb, const Window& w, const Per
 
 // The reducing workgroup: maximum over the pairs' slots of every round, published as the decision.
 __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Persist& ps, unsigned long long* red,
-                                    float* lat_win, int* timed_out) {
+                                    float* lat_win, float* swap_win, int* timed_out) {
   const int tid = threadIdx.x;
   const int B = tb.B;
   const int my_slot = tid < ps.n_pairs ? tid : 0;
@@ -145,15 +147,17 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
   for (int rl = 0; rl < ps.n_rounds; ++rl) {
     const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
     unsigned long long mine = 0ull;
-    float mine_lat = 0.f;
+    float mine_lat = 0.f, mine_swap = 0.f;
     for (int i = tid; i < ps.n_pairs; i += kRoundThreads) {
-      const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + i) * 2;
-      unsigned long long v0 = 0ull, v1 = 0ull;
+      const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + i) * 4;
+      unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull;
       bool ok = false;
       for (int k = 0; k < kSpinLimit; ++k) {
         v0 = ld_dev(slot);
         v1 = ld_dev(slot + 1);
-        ok = ((uint32_t)(v0 >> 9) & kGenMask) == (gen & kGenMask) && (uint32_t)(v1 & 0xFFFFFFFFull) == gen;
+        v2 = ld_dev(slot + 2);
+        ok = ((uint32_t)(v0 >> 9) & kGenMask) == (gen & kGenMask) && (uint32_t)(v1 & 0xFFFFFFFFull) == gen &&
+             (uint32_t)(v2 & 0xFFFFFFFFull) == gen;
         if (ok) break;
         __builtin_amdgcn_s_sleep(1);
       }
@@ -163,26 +167,34 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
         const int pa = i == tid ? my_a : ps.pair_app[i], pm = i == tid ? my_m : ps.pair_model[i];
         const uint32_t cid = (uint32_t)((pa * tb.Mmax + pm) * B) + (uint32_t)(v0 & 0xffull);
         const unsigned long long pk = pack_candidate(__uint_as_float((uint32_t)(v0 >> 32)), cid);
-        if (pk > mine) { mine = pk; mine_lat = __uint_as_float((uint32_t)(v1 >> 32)); }
+        if (pk > mine) {
+          mine = pk;
+          mine_lat = __uint_as_float((uint32_t)(v1 >> 32));
+          mine_swap = __uint_as_float((uint32_t)(v2 >> 32));
+        }
       }
     }
     const unsigned long long all = block_max_u64(mine, red);
-    if (all != 0ull && mine == all) *lat_win = mine_lat;      // candidate ids are unique: one writer
+    if (all != 0ull && mine == all) {                         // candidate ids are unique: one writer
+      *lat_win = mine_lat;
+      *swap_win = mine_swap;
+    }
     __syncthreads();
     if (*timed_out) {
       if (tid == 0) atomicOr(&w.st->err, kErrSync);
       break;
     }
     if (tid == 0) {
-      unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 2;
+      unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 4;
       const uint32_t cidp1 = all != 0ull ? (0xFFFFFFFFu - (uint32_t)(all & 0xFFFFFFFFull)) + 1u : 0u;
       st_dev(d, ((unsigned long long)__float_as_uint(all != 0ull ? *lat_win : 0.f) << 32) | (unsigned long long)gen);
       st_dev(d + 1, ((unsigned long long)cidp1 << 32) | (unsigned long long)gen);
+      st_dev(d + 2, ((unsigned long long)__float_as_uint(all != 0ull ? *swap_win : 0.f) << 32) | (unsigned long long)gen);
       st_dev(ps.dec + rl, all | (1ull << 63));
       ps.ticks[rl + 1] = wall_clock64();
     }
     if (all == 0ull) break;                                    // nothing live anywhere
-    __syncthreads();                                           // lat_win is rewritten next round
+    __syncthreads();                                           // lat_win and swap_win are rewritten next round
   }
 }
 
@@ -193,13 +205,13 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   __shared__ int32_t wave_cnt[kRoundThreads / 64], keep_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
   __shared__ double dsum[kRoundThreads];
-  __shared__ float lat_win;
+  __shared__ float lat_win, swap_win;
   __shared__ uint32_t cid_win;
   __shared__ int timed_out;
   State* st = w.st;
   if (st->done || st->err) return;          // the state is rewritten only when the commit workgroup ends
   if ((int)blockIdx.x >= ps.n_pairs) {
-    if ((int)blockIdx.x == ps.n_pairs) persist_reduce_loop(tb, w, ps, red, &lat_win, &timed_out);
+    if ((int)blockIdx.x == ps.n_pairs) persist_reduce_loop(tb, w, ps, red, &lat_win, &swap_win, &timed_out);
     if ((int)blockIdx.x == ps.n_pairs + 1) persist_commit_loop(tb, w, ps, dsum, red);
     return;
   }
@@ -209,6 +221,8 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   const int B = tb.B, cap = kWinCap;
   const int kind = tb.penalty[a];
   const float lmin = tb.lmin[a];
+  const float my_swap = tb.swap[a * tb.Mmax + m];
+  int prev_a = st->last.app, prev_m = st->last.model;       // -1 before the window's first batch
   const int seg_e = w.seg[a + 1];
   int r = st->round;
   double t = st->t;
@@ -314,14 +328,17 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
 
     // ---- triangle: the same code as k_round_score ----
     unsigned long long best = 0ull;
-    if (nbe > 0) best = triangle_best(kind, ent, lat_s, nbe, B, t, (uint32_t)((a * tb.Mmax + m) * B), nullptr);
+    const float swap_now = (prev_a == a && prev_m == m) ? 0.f : my_swap;
+    if (nbe > 0)
+      best = triangle_best(kind, ent, lat_s, nbe, B, t + (double)swap_now, (uint32_t)((a * tb.Mmax + m) * B), nullptr);
     best = block_max_u64(best, red);
 
     // ---- publish this pair's best candidate ----
     if (tid == 0) {
-      unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + pair) * 2;
+      unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + pair) * 4;
       const bool valid = best != 0ull;
       const int b = valid ? (int)((0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull)) % (uint32_t)B) + 1 : 1;
+      st_dev(slot + 2, ((unsigned long long)__float_as_uint(swap_now) << 32) | (unsigned long long)gen);
       st_dev(slot + 1, ((unsigned long long)__float_as_uint(lat_s[b - 1]) << 32) | (unsigned long long)gen);
       st_dev(slot, slot_word0(__uint_as_float((uint32_t)(best >> 32)), gen, valid, b));
     }
@@ -332,19 +349,22 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
 
     // ---- wait for the decision ----
     if (tid == 0) {
-      const unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 2;
-      unsigned long long v0 = 0ull, v1 = 0ull;
+      const unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 4;
+      unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull;
       bool ok = false;
       for (int k = 0; k < kSpinLimit; ++k) {
         v0 = ld_dev(d);
         v1 = ld_dev(d + 1);
-        ok = (uint32_t)(v0 & 0xFFFFFFFFull) == gen && (uint32_t)(v1 & 0xFFFFFFFFull) == gen;
+        v2 = ld_dev(d + 2);
+        ok = (uint32_t)(v0 & 0xFFFFFFFFull) == gen && (uint32_t)(v1 & 0xFFFFFFFFull) == gen &&
+             (uint32_t)(v2 & 0xFFFFFFFFull) == gen;
         if (ok) break;
         __builtin_amdgcn_s_sleep(1);
       }
       if (!ok) timed_out = 1;
       lat_win = __uint_as_float((uint32_t)(v0 >> 32));
       cid_win = (uint32_t)(v1 >> 32);
+      swap_win = __uint_as_float((uint32_t)(v2 >> 32));
     }
     __syncthreads();
     if (timed_out) {
@@ -352,14 +372,15 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
       break;
     }
     const uint32_t cidp1 = cid_win;
-    const float lat_sel = lat_win;
+    const float lat_sel = lat_win, swap_sel = swap_win;
     __syncthreads();                                         // both are rewritten next round
     if (cidp1 == 0u) break;                                  // nothing live anywhere
     const uint32_t cid = cidp1 - 1u;
     const int bsel = (int)(cid % (uint32_t)B) + 1;
-    const int asel = (int)(cid / (uint32_t)B) / tb.Mmax;
+    const int asel = (int)(cid / (uint32_t)B) / tb.Mmax, msel = (int)(cid / (uint32_t)B) % tb.Mmax;
     shift = asel == a ? bsel : 0;
-    t = t + (double)lat_sel;
+    t = (t + (double)swap_sel) + (double)lat_sel;
+    prev_a = asel; prev_m = msel;
     r += 1;
   }
   // first position of this application that may still be live, for whoever continues the window

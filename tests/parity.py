@@ -83,7 +83,7 @@ def replay(profile, requests, ea_ref, key_ref, log, members, done, tol):
         assert abs(rec["t_start_ms"] - win.t) <= 1e-9 * max(1.0, abs(win.t)), f"round {r}: clock {rec['t_start_ms']} vs {win.t}"
         exact = (d["app"], d["model"], d["batch"]) == (a, m, b) and np.array_equal(d["ids"], ids)
         kind = int(profile.penalty[a])
-        t_end = win.t + win.lat[a][m, b - 1]
+        t_end = win.start_time(a, m) + win.lat[a][m, b - 1]
         mine = float((win.key[ids] * orc.utility(win.ea[ids, m], kind, win.D[ids], t_end)).sum())
         if exact:
             stats["exact"] += 1

@@ -303,6 +303,43 @@ def test_round_by_round_equals_schedule_and_is_deterministic(gpu):
     b["close"]()
 
 
+@pytest.mark.parametrize("kind", [wl.PEN_STEP, wl.PEN_LINEAR, wl.PEN_SIGMOID])
+def test_swap_in_costs_on_both_round_paths(gpu, kind):
+    """Sec. 3.1 "context switch time" / Sec. 5.2 model locality: a batch pays its variant's swap-in cost
+    unless the previous batch ran the same variant."""
+    torch, binding = gpu
+    w = wl.tiny(seed=95 + kind, n=2600, classes=(5, 3, 40, 2), models=(3, 2, 8, 5), max_batch=21, feat_dim=19,
+                penalty=kind, deadline=(4.0, 120.0), fractions=(0.4, 0.1, 0.3, 0.2))
+    wl.attach_swap_costs(w.profile, seed=96, lo=0.5, hi=9.0, skip_every=3)
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True)       # sp_schedule: rounds in one launch
+    # swap costs do show in the clock: some batch starts computing later than the previous one ended
+    L = w.profile.lat_ms
+    paid = [r for r in got["log"] if r["t_end_ms"] - r["t_start_ms"] > float(L[r["app"]][r["model"], r["batch"] - 1]) * (1 + 1e-6)]
+    free = [r for r in got["log"] if r not in paid]
+    assert paid and free
+    # the same window one round per call (two kernels per round)
+    ctx = binding.Context(w.profile, 2600)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_score(x, app, D, wt)
+    for rec in got["log"]:
+        rc, dec = ctx.sp_greedy_round()
+        assert rc == binding.SP_OK and dec == rec
+    assert ctx.sp_greedy_round()[0] == binding.SP_DONE
+    # costs can be taken away again, and bad ones are rejected
+    for a in range(4):
+        ctx.sp_set_swap_cost(a, None)
+    ctx.sp_score(x, app, D, wt)
+    rc, summ, log = ctx.sp_schedule(0, log_capacity=4096)
+    assert all(r["t_end_ms"] - r["t_start_ms"] == pytest.approx(float(L[r["app"]][r["model"], r["batch"] - 1]), rel=1e-6) for r in log)
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_set_swap_cost(0, np.array([1.0, -2.0, 0.0], dtype=np.float32))
+    assert e.value.status == binding.SP_EINVAL
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_set_swap_cost(9, np.array([1.0], dtype=np.float32))
+    assert e.value.status == binding.SP_EINVAL
+    ctx.close()
+
+
 def test_context_reuse_with_a_smaller_second_window(gpu):
     torch, binding = gpu
     big = wl.make("cfg2", n_requests=3000)
