@@ -212,7 +212,8 @@ def score_requests(profile, requests, chunk=16384, return_theta=False):
 
 
 def service_order(app, key, n_apps):
-    """Per application, request ids by (key descending, id ascending)."""
+    """Per application, request ids by (key descending, id ascending).  Earliest deadline first is this
+    with the negated deadline as the key."""
     out = []
     for a in range(int(n_apps)):
         sel = np.nonzero(np.asarray(app) == a)[0]
@@ -227,7 +228,7 @@ class Window:
     """State of one scheduling window: who is still pending, the worker clock
     t (ms since the window's start), and what has been assigned so far."""
 
-    def __init__(self, profile, requests, ea=None, key=None):
+    def __init__(self, profile, requests, ea=None, key=None, policy=None):
         self.p = profile
         self.n = int(requests.app.shape[0])
         self.app = np.asarray(requests.app)
@@ -237,7 +238,16 @@ class Window:
             ea, key = score_requests(profile, requests)
         self.ea = np.asarray(ea, dtype=np.float64)
         self.key = np.asarray(key, dtype=np.float64)
-        self.order = service_order(self.app, self.key, profile.n_apps)
+        # policy knobs (Sec. 6.1 baselines, Alg. 1); plain integer codes, 0 everywhere = the default
+        g = (lambda name: int(getattr(policy, name, 0))) if policy is not None else (lambda name: 0)
+        self.edf, self.group_first, self.whole = g("order") == 1, g("select") == 1, g("batch_rule") == 1
+        self.max_accuracy, self.unit_weight = g("choice") == 1, g("weight") == 1
+        cap = g("batch_cap")
+        self.B = min(int(profile.max_batch), cap) if cap > 0 else int(profile.max_batch)
+        # what orders requests inside an application, and what a group's priority averages (eq. 14)
+        self.omega = -self.D if self.edf else self.key
+        self.order = service_order(self.app, self.omega, profile.n_apps)
+        self.wsum = np.ones(self.n) if self.unit_weight else self.key
         self.lat = [widen(l) for l in profile.lat_ms]
         self.lmin = [float(l[:, 0].min()) for l in self.lat]
         # cost of bringing a variant in (Sec. 3.1: latency "including any context switch time"; Sec. 5.2:
@@ -266,7 +276,17 @@ class Window:
         return ids[~dead]
 
     def candidate_window(self, a):
-        return self.live_queue(a)[: int(self.p.max_batch)]
+        return self.live_queue(a)[: self.B]
+
+    def scoring_penalty(self, a):
+        """Penalty kind the candidates are compared under: the application's own (eq. 13), or the step
+        penalty when variants are compared by accuracy among those that meet the deadline."""
+        return PEN_STEP if self.max_accuracy else int(self.p.penalty[a])
+
+    def group_priority(self, a):
+        """eq. (14) over the application's candidate window; None when it is empty."""
+        q = self.candidate_window(a)
+        return None if q.shape[0] == 0 else float(np.mean(self.omega[q]))
 
     def start_time(self, a, m):
         """When a batch on variant m of application a starts computing: now, plus the swap-in cost
@@ -279,7 +299,7 @@ class Window:
     def score_cube(self):
         """Score[a, m, b-1] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
         over the first b live requests of a; -inf where (a,m,b) is not a candidate."""
-        A, B = int(self.p.n_apps), int(self.p.max_batch)
+        A, B = int(self.p.n_apps), int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
         m_max = int(np.max(self.p.n_models))
         cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
         for a in range(A):
@@ -287,12 +307,14 @@ class Window:
             nb = q.shape[0]
             if nb == 0:
                 continue
-            kind = int(self.p.penalty[a])
+            kind = self.scoring_penalty(a)
             for m in range(int(self.p.n_models[a])):
                 for b in range(1, nb + 1):
+                    if self.whole and b != nb:
+                        continue
                     e = self.start_time(a, m) + self.lat[a][m, b - 1]
                     members = q[:b]
-                    terms = self.key[members] * utility(self.ea[members, m], kind, self.D[members], e)
+                    terms = self.wsum[members] * utility(self.ea[members, m], kind, self.D[members], e)
                     cube[a, m, b - 1] = terms.sum()
         return cube
 
@@ -300,7 +322,7 @@ class Window:
         """Same numbers as score_cube with the (b, j) triangle done as one
         masked array per (a, m); kept beside the loop version so that a test
         can check one against the other."""
-        A, B = int(self.p.n_apps), int(self.p.max_batch)
+        A, B = int(self.p.n_apps), int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
         m_max = int(np.max(self.p.n_models))
         cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
         for a in range(A):
@@ -308,13 +330,15 @@ class Window:
             nb = q.shape[0]
             if nb == 0:
                 continue
-            kind = int(self.p.penalty[a])
+            kind = self.scoring_penalty(a)
             tri = np.tril(np.ones((nb, nb), dtype=bool))          # [b, j]: j <= b
             for m in range(int(self.p.n_models[a])):
                 e = self.start_time(a, m) + self.lat[a][m, :nb]    # [b]
                 u = utility(self.ea[q, m][None, :], kind, self.D[q][None, :], e[:, None])
-                terms = np.where(tri, self.key[q][None, :] * u, 0.0)
+                terms = np.where(tri, self.wsum[q][None, :] * u, 0.0)
                 cube[a, m, :nb] = terms.sum(axis=1)
+                if self.whole:
+                    cube[a, m, : nb - 1] = -np.inf
         return cube
 
     def decide(self, cube=None):
@@ -324,6 +348,15 @@ class Window:
             cube = self.score_cube_fast()
         if not np.isfinite(cube).any():
             return None
+        if self.group_first:
+            # Alg. 1: the group with the highest mean priority goes first (ties: smallest application),
+            # then the variant (and batch size) is chosen for that group alone
+            prio = [self.group_priority(a) for a in range(cube.shape[0])]
+            best = max(v for v in prio if v is not None)
+            a_star = min(a for a, v in enumerate(prio) if v is not None and v == best)
+            masked = np.full_like(cube, -np.inf)
+            masked[a_star] = cube[a_star]
+            cube = masked
         flat = int(np.argmax(cube))            # first maximum in C order = smallest (a,m,b)
         a, m, bi = np.unravel_index(flat, cube.shape)
         b = int(bi) + 1
@@ -337,7 +370,7 @@ class Window:
         """Serve requests `ids` of application a as one batch on variant m."""
         ids = np.asarray(ids, dtype=np.int64)
         b = int(ids.shape[0])
-        assert 1 <= b <= int(self.p.max_batch)
+        assert 1 <= b <= self.B
         assert np.all(self.app[ids] == a) and np.all(self.alive[ids])
         t_end = self.start_time(a, m) + self.lat[a][m, b - 1]
         u = utility(self.ea[ids, m], int(self.p.penalty[a]), self.D[ids], t_end)

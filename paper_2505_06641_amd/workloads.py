@@ -58,6 +58,37 @@ class Profile:
     swap_ms: Optional[List[Optional[np.ndarray]]] = None
 
 
+# Scheduling policy knobs (Sec. 6.1 "Baselines and Metrics", Alg. 1).  Plain codes shared by the C ABI,
+# the binding and the oracle; no arithmetic here.
+ORDER_PRIORITY, ORDER_EDF = 0, 1            # service order inside an application: eq. (12) key, or earliest deadline first
+SELECT_JOINT, SELECT_GROUP_FIRST = 0, 1     # one arg max over (a, m, b), or first the group by its mean priority (eq. 14)
+BATCH_FREE, BATCH_WHOLE = 0, 1              # any batch size up to the cap, or the whole candidate window (groups run whole)
+CHOICE_UTILITY, CHOICE_MAX_ACCURACY = 0, 1  # variants compared by utility (eq. 13), or by accuracy among those on time
+WEIGHT_KEY, WEIGHT_UNIT = 0, 1              # utilities of a batch summed with the requests' keys as weights, or plainly
+
+
+@dataclass
+class Policy:
+    order: int = ORDER_PRIORITY
+    select: int = SELECT_JOINT
+    batch_rule: int = BATCH_FREE
+    choice: int = CHOICE_UTILITY
+    weight: int = WEIGHT_KEY
+    batch_cap: int = 0                      # > 0: batches of at most this many requests
+
+
+def named_policy(name: str) -> Policy:
+    """The approaches of Sec. 6.1 in terms of the knobs above (the data-oblivious ones additionally
+    replace the posterior by the profiling label mix: a prior with no evidence)."""
+    return {
+        "sneakpeek": Policy(),
+        "alg1": Policy(select=SELECT_GROUP_FIRST, batch_rule=BATCH_WHOLE, weight=WEIGHT_UNIT),
+        "lo_priority": Policy(select=SELECT_GROUP_FIRST, batch_cap=1),
+        "lo_edf": Policy(order=ORDER_EDF, select=SELECT_GROUP_FIRST, batch_cap=1),
+        "maxacc_edf": Policy(order=ORDER_EDF, select=SELECT_GROUP_FIRST, choice=CHOICE_MAX_ACCURACY, batch_cap=1),
+    }[name]
+
+
 @dataclass
 class Requests:
     """Pending requests of one scheduling window (Sec. 3.1)."""
