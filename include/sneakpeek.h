@@ -210,6 +210,41 @@ sp_status sp_get_round_times(sp_ctx* ctx, float* ms_out_host, int32_t capacity, 
 sp_status sp_set_prior(sp_ctx* ctx, int32_t app, const float* alpha_host, float evidence_k);
 
 /*
+ * Scheduling policy: the approaches the paper compares (Sec. 6.1 "Baselines and Metrics") and Alg. 1 as
+ * printed, as combinations of independent knobs on the same kernels.  All zero (or policy == NULL) is the
+ * default: priority order, one joint arg max over (application, variant, batch size).
+ *   order       SP_ORDER_PRIORITY: requests of an application are served by descending key (eq. (12));
+ *               SP_ORDER_EDF: by ascending deadline (ties: ascending request id).
+ *   select      SP_SELECT_JOINT: arg max of the score over all (a, m, b);
+ *               SP_SELECT_GROUP_FIRST: first the application whose candidate window has the highest mean
+ *               priority (eq. (14); the mean of the keys, or of the negated deadlines under EDF; ties: the
+ *               smallest application), then the arg max over (m, b) for that application alone (Alg. 1).
+ *   batch_rule  SP_BATCH_FREE: every batch size up to the cap is a candidate;
+ *               SP_BATCH_WHOLE: only the whole candidate window ("all requests in the group", Alg. 1).
+ *   choice      SP_CHOICE_UTILITY: candidates are compared by utility under the application's penalty
+ *               (eq. (13)); SP_CHOICE_MAX_ACCURACY: under the step penalty, i.e. by accuracy among the
+ *               variants that meet the deadline ("Max Accuracy"); utilities of served requests always use
+ *               the application's own penalty.
+ *   weight      SP_WEIGHT_KEY: a batch's score is the key-weighted sum of its members' utilities;
+ *               SP_WEIGHT_UNIT: the plain sum ("avg group utility", Alg. 1).
+ *   batch_cap   > 0: batches hold at most min(batch_cap, B) requests (1 = request-level baselines).
+ * LO-Priority = {GROUP_FIRST, cap 1}; LO-EDF = {EDF, GROUP_FIRST, cap 1}; MaxAcc-EDF = LO-EDF +
+ * MAX_ACCURACY; Alg. 1 = {GROUP_FIRST, WHOLE, UNIT}; the data-oblivious variants also set a prior with no
+ * evidence (sp_set_prior with the profiling label mix and evidence_k = 0).
+ * The window must be scored again afterwards (the service order depends on the policy): rounds return
+ * SP_ESTATE until then.  SP_EINVAL: a knob out of range.
+ */
+typedef enum { SP_ORDER_PRIORITY = 0, SP_ORDER_EDF = 1 } sp_order;
+typedef enum { SP_SELECT_JOINT = 0, SP_SELECT_GROUP_FIRST = 1 } sp_select;
+typedef enum { SP_BATCH_FREE = 0, SP_BATCH_WHOLE = 1 } sp_batch_rule;
+typedef enum { SP_CHOICE_UTILITY = 0, SP_CHOICE_MAX_ACCURACY = 1 } sp_choice;
+typedef enum { SP_WEIGHT_KEY = 0, SP_WEIGHT_UNIT = 1 } sp_weight;
+typedef struct {
+  int32_t order, select, batch_rule, choice, weight, batch_cap;
+} sp_policy;
+sp_status sp_set_policy(sp_ctx* ctx, const sp_policy* policy);
+
+/*
  * Swap-in cost of the variants of one application (Sec. 3.1: a variant's latency "including any context
  * switch time"; Sec. 5.2: grouping exploits model locality and avoids swapping models in and out).
  * swap_ms_host: HOST pointer to M_a values >= 0 (copied), or NULL for none.  A batch on variant m of that

@@ -21,8 +21,13 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch", "sp_set_prior", "sp_set_swap_cost",
+           "sp_rounds_in_one_launch", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
+
+
+class sp_policy(C.Structure):
+    _fields_ = [("order", C.c_int32), ("select", C.c_int32), ("batch_rule", C.c_int32), ("choice", C.c_int32),
+                ("weight", C.c_int32), ("batch_cap", C.c_int32)]
 
 
 class sp_profile(C.Structure):
@@ -100,6 +105,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_max_classes.restype = C.c_int32
     lib.sp_set_prior.argtypes = [vp, C.c_int32, C.c_void_p, C.c_float]
     lib.sp_set_prior.restype = C.c_int
+    lib.sp_set_policy.argtypes = [vp, C.POINTER(sp_policy)]
+    lib.sp_set_policy.restype = C.c_int
     lib.sp_set_swap_cost.argtypes = [vp, C.c_int32, C.c_void_p]
     lib.sp_set_swap_cost.restype = C.c_int
     lib.sp_rounds_in_one_launch.argtypes = [vp]
@@ -182,7 +189,7 @@ def _stream_ptr(stream):
 class Context:
     """One sp_ctx.  Methods carry the names of the C entry points."""
 
-    def __init__(self, profile, max_requests: int, device: int = 0):
+    def __init__(self, profile, max_requests: int, device: int = 0, policy=None):
         self.lib = load_library()
         self.profile = profile
         self.device = device
@@ -197,6 +204,8 @@ class Context:
         self.c_max = self.lib.sp_max_classes(h)
         self.rounds_in_one_launch = bool(self.lib.sp_rounds_in_one_launch(h))
         self.n = 0
+        if policy is not None:
+            self.sp_set_policy(policy)
         if getattr(profile, "swap_ms", None) is not None:
             for a in range(int(profile.n_apps)):
                 if profile.swap_ms[a] is not None:
@@ -256,6 +265,14 @@ class Context:
         buf = np.ascontiguousarray(alpha, dtype=np.float32)
         return self._check(self.lib.sp_set_prior(self.h, int(app), buf.ctypes.data_as(C.c_void_p),
                                                  C.c_float(float(evidence_k))), "sp_set_prior")
+
+    def sp_set_policy(self, policy):
+        """policy: an object with the fields of sp_policy (workloads.Policy), or None for the default."""
+        if policy is None:
+            return self._check(self.lib.sp_set_policy(self.h, None), "sp_set_policy")
+        st = sp_policy(int(policy.order), int(policy.select), int(policy.batch_rule), int(policy.choice),
+                       int(policy.weight), int(policy.batch_cap))
+        return self._check(self.lib.sp_set_policy(self.h, C.byref(st)), "sp_set_policy")
 
     def sp_set_swap_cost(self, app, swap_ms):
         """swap_ms: host array of M_a floats, or None for no swap-in cost."""

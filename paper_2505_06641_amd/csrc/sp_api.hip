@@ -221,6 +221,8 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   Tables& tb = c->tb;
   tb.A = A; tb.d = c->d; tb.H = c->H; tb.B = B; tb.Mmax = Mmax; tb.Cmax = Cmax; tb.dtype = c->dtype;
   tb.inv_timescale = 1.0f / p->prio_timescale_ms;
+  tb.pol_edf = tb.pol_group_first = tb.pol_whole = tb.pol_max_accuracy = tb.pol_unit_weight = 0;
+  tb.Bcap = B;
   sp_status s;
   std::vector<int32_t> ncls(p->n_classes, p->n_classes + A), nmod(p->n_models, p->n_models + A),
       pen(p->penalty, p->penalty + A), acc_off(A);
@@ -286,6 +288,7 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &w.order_of, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.util, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.cand, (size_t)A * Mmax)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.cand_prio, (size_t)A * Mmax)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.win_pos, (size_t)A * B)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.win_n, A)) != SP_OK) return s;
   w.log_cap = (int32_t)std::max<size_t>(N, 1);
@@ -388,7 +391,7 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
     for (int m = 0; m < p->n_models[a]; ++m) { pa.push_back(a); pm.push_back(m); }
   const size_t n_pairs = pa.size();
   const size_t ring = (size_t)kPersistRounds * A * c->B;
-  if (n_pairs == 0 || n_pairs > 4096 || ring > ((size_t)32 << 20)) return SP_OK;
+  if (n_pairs == 0 || n_pairs > (size_t)kMaxPairs || ring > ((size_t)32 << 20)) return SP_OK;
   int cus = 0, per_cu = 0, rate_khz = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) return SP_OK;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent, kRoundThreads, 0) != hipSuccess) {
@@ -643,7 +646,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       std::swap(v_out, v_spare);
     }
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
-                       (const uint32_t*)k_in, (const int32_t*)curV, w);
+                       (const uint32_t*)k_in, (const int32_t*)curV, w, c->tb.pol_edf);
     if (tm) {
       SP_HIP(c, hipEventRecord(c->ev[3], s));
       c->timed_score = true;
@@ -877,6 +880,21 @@ sp_status sp_set_prior(sp_ctx* c, int32_t app, const float* alpha_host, float ev
   SP_HIP(c, hipDeviceSynchronize());
   SP_HIP(c, hipMemcpy(c->d_ea_gain + app, &gain, sizeof(float), hipMemcpyHostToDevice));
   SP_HIP(c, hipMemcpy(c->d_ea_bias + (size_t)app * c->Mmax, bias.data(), bias.size() * sizeof(float), hipMemcpyHostToDevice));
+  return SP_OK;
+}
+
+sp_status sp_set_policy(sp_ctx* c, const sp_policy* p) {
+  if (!c) return SP_EINVAL;
+  sp_policy def{};
+  if (!p) p = &def;
+  if (p->order < 0 || p->order > 1 || p->select < 0 || p->select > 1 || p->batch_rule < 0 || p->batch_rule > 1 ||
+      p->choice < 0 || p->choice > 1 || p->weight < 0 || p->weight > 1 || p->batch_cap < 0)
+    return SP_EINVAL;
+  Tables& tb = c->tb;
+  tb.pol_edf = p->order; tb.pol_group_first = p->select; tb.pol_whole = p->batch_rule;
+  tb.pol_max_accuracy = p->choice; tb.pol_unit_weight = p->weight;
+  tb.Bcap = p->batch_cap > 0 ? std::min(p->batch_cap, c->B) : c->B;
+  c->scored = false;                 // the service order depends on the policy: score the window again
   return SP_OK;
 }
 

@@ -18,6 +18,13 @@ constexpr uint32_t kErrSync = 8u;       // a bounded wait between resident workg
 // Immutable per-context tables (device pointers).
 struct Tables {
   int32_t A, d, H, B, Mmax, Cmax, dtype;
+  // policy knobs (Sec. 6.1 baselines, Alg. 1); all zero = the default policy, Bcap = B
+  int32_t pol_edf;            // 1: requests of an application are served earliest deadline first
+  int32_t pol_group_first;    // 1: first the application with the highest mean priority (eq. 14), then (m, b)
+  int32_t pol_whole;          // 1: only the whole candidate window is a candidate batch
+  int32_t pol_max_accuracy;   // 1: candidates are compared under the step penalty
+  int32_t pol_unit_weight;    // 1: utilities of a batch are summed without the keys as weights
+  int32_t Bcap;               // largest batch (<= B)
   float inv_timescale;
   const int32_t* n_classes;   // [A]
   const int32_t* n_models;    // [A]
@@ -84,6 +91,7 @@ struct Window {
   int32_t* order_of;          // [n]
   float* util;                // [n]
   unsigned long long* cand;   // [A, Mmax] best packed candidate per (a, m) of the running round
+  float* cand_prio;           // [A, Mmax] group priority (eq. 14) of the application's window, per (a, m)
   int32_t* win_pos;           // [A, B] service positions of each app's candidate window
   int32_t* win_n;             // [A]
   Decision* log;              // [log_cap]

@@ -22,6 +22,18 @@ namespace sp {
 constexpr int kRoundThreads = 512;
 constexpr int kPairLanes = 8;                       // lanes that share one pair of batch sizes in the triangle
 
+__device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
+  // fixed-order tree: the result does not depend on scheduling
+  __syncthreads();
+  scratch[threadIdx.x] = v;
+  __syncthreads();
+  for (int o = kRoundThreads / 2; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) scratch[threadIdx.x] += scratch[threadIdx.x + o];
+    __syncthreads();
+  }
+  return scratch[0];
+}
+
 // When a batch on variant m of application a starts computing: now, plus the variant's swap-in cost
 // unless the previous batch of the window ran the same variant (Sec. 3.1 "context switch time";
 // Sec. 5.2 model locality).  prev.app is -1 before the first batch.
@@ -56,7 +68,7 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 // Every kernel that scores rounds calls this function: their scores agree bit for bit.
 template <int KIND>
 __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* ent, const float* lat, int nb, int B,
-                                                                double t, uint32_t cid0, float* cube_out) {
+                                                                double t, uint32_t cid0, float* cube_out, int only_b) {
   const int tid = threadIdx.x;
   const int sub = tid % kPairLanes, grp = tid / kPairLanes;
   const int n_pairs = (B + 1) / 2;
@@ -66,7 +78,9 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
     const double E1 = t + (double)lat[b1 - 1], E2 = t + (double)lat[b2 - 1];
     const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
     const float e2h = (float)E2, e2l = (float)(E2 - (double)e2h);
-    const int n1 = b1 <= nb ? b1 : 0, n2 = (b2 <= nb && b2 != b1) ? b2 : 0;
+    // only_b > 0: that batch size alone is a candidate ("the group runs whole")
+    const int n1 = (b1 <= nb && (only_b == 0 || b1 == only_b)) ? b1 : 0;
+    const int n2 = (b2 <= nb && b2 != b1 && (only_b == 0 || b2 == only_b)) ? b2 : 0;
     float s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int j = sub;
     for (; j < n1 && j < n2; j += kPairLanes) {                 // both batch sizes use request j
@@ -110,16 +124,33 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
 }
 
 __device__ __forceinline__ unsigned long long triangle_best(int kind, const float4* ent, const float* lat, int nb, int B,
-                                                           double t, uint32_t cid0, float* cube_out) {
-  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out);
-  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out);
-  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out);
+                                                           double t, uint32_t cid0, float* cube_out, int only_b) {
+  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b);
+  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b);
+  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b);
+}
+
+// Penalty kind the candidates of application a are compared under: its own (eq. 13), or the step penalty
+// when variants are compared by accuracy among those that meet the deadline (Sec. 6.1 "Max Accuracy").
+__device__ __forceinline__ int scoring_penalty(const Tables& tb, int kind) { return tb.pol_max_accuracy ? 0 : kind; }
+
+// What orders the requests of an application and what a group's priority averages (eq. 14): the key of
+// eq. (12), or the negated deadline (earliest deadline first).
+__device__ __forceinline__ float ordering_value(const Tables& tb, const Window& w, int pos) {
+  return tb.pol_edf ? -w.D_s[pos] : w.key_s[pos];
+}
+
+// Order-preserving map of a float onto unsigned integers (negative values included).
+__device__ __forceinline__ uint32_t ordered_bits(float v) {
+  const uint32_t b = __float_as_uint(v);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
 // One window entry from the request at service position pos, for variant m.
 __device__ __forceinline__ float4 window_entry(const Tables& tb, const Window& w, int pos, int m) {
   const float D = w.D_s[pos];
-  return make_float4(w.key_s[pos] * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m], D, 1.0f / D, 2.0f * D);
+  const float wgt = tb.pol_unit_weight ? 1.0f : w.key_s[pos];
+  return make_float4(wgt * w.ea[(int64_t)w.id_s[pos] * tb.Mmax + m], D, 1.0f / D, 2.0f * D);
 }
 
 __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window w, float* __restrict__ cube_out) {
@@ -127,11 +158,12 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   __shared__ float4 ent[kMaxBatch];
   __shared__ int32_t wave_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
+  __shared__ double dsum[kRoundThreads];
   const State* st = w.st;
   if (st->done || st->err) return;
   const int a = blockIdx.x / tb.Mmax, m = blockIdx.x % tb.Mmax;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int M = tb.n_models[a], B = tb.B;
+  const int M = tb.n_models[a], B = tb.B, Bw = tb.Bcap;   // B: row stride of the tables; Bw: largest batch
   if (m >= M) {
     if (tid == 0) w.cand[blockIdx.x] = 0ull;
     return;
@@ -150,7 +182,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   // entries, so whole vectors can always be loaded.
   int found = 0;
   int base = head & ~3;
-  for (int step = 0; base < seg_e && found < B; ++step) {
+  for (int step = 0; base < seg_e && found < Bw; ++step) {
     const int nq = step == 0 ? 1 : 4;                  // groups of 4 positions per thread
     const int p0 = base + 4 * nq * tid;
     uint32_t mask = 0;
@@ -184,7 +216,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     }
     int rank = before + incl - cnt;
     uint32_t mk = mask;
-    while (mk != 0 && rank < B) {
+    while (mk != 0 && rank < Bw) {
       const int j = __ffs((int)mk) - 1;
       mk &= mk - 1;
       win[rank++] = p0 + j;
@@ -193,7 +225,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     base += 4 * nq * kRoundThreads;
     __syncthreads();
   }
-  const int nb = min(found, B);
+  const int nb = min(found, Bw);
   if (m == 0) {
     for (int j = tid; j < nb; j += kRoundThreads) w.win_pos[a * B + j] = win[j];
     if (tid == 0) {
@@ -209,21 +241,15 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   __syncthreads();
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
   const double t0 = start_time(tb, st->last, t, a, m);
-  unsigned long long best = triangle_best(kind, ent, lat, nb, B, t0, (uint32_t)((a * tb.Mmax + m) * B), cube_out);
+  unsigned long long best = triangle_best(scoring_penalty(tb, kind), ent, lat, nb, Bw, t0,
+                                          (uint32_t)((a * tb.Mmax + m) * B), cube_out, tb.pol_whole ? nb : 0);
+  if (tb.pol_group_first) {
+    // the group's priority (eq. 14) over the window; the same fixed-order sum in every kernel that forms it
+    const double ps = block_sum_f64(tid < nb ? (double)ordering_value(tb, w, win[tid]) : 0.0, dsum);
+    if (tid == 0) w.cand_prio[blockIdx.x] = (float)(ps / (double)nb);
+  }
   best = block_max_u64(best, red);
   if (tid == 0) w.cand[blockIdx.x] = best;
-}
-
-__device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
-  // fixed-order tree: the result does not depend on scheduling
-  __syncthreads();
-  scratch[threadIdx.x] = v;
-  __syncthreads();
-  for (int o = kRoundThreads / 2; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) scratch[threadIdx.x] += scratch[threadIdx.x + o];
-    __syncthreads();
-  }
-  return scratch[0];
 }
 
 // Members of one batch: outputs, pending flags and the three sums.  pos_of(j) gives the service position
@@ -271,6 +297,25 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   if (best == 0ull) {                 // nothing live anywhere
     if (tid == 0) st->done = 1;
     return;
+  }
+  if (tb.pol_group_first) {
+    // Alg. 1: first the application with the highest group priority (ties: the smallest application),
+    // then the best candidate of that application alone
+    unsigned long long top = 0ull;
+    for (int i = tid; i < n_cand; i += kRoundThreads)
+      if (w.cand[i] != 0ull) {
+        const unsigned long long pk = ((unsigned long long)ordered_bits(w.cand_prio[i]) << 32) |
+                                      (unsigned long long)(0xFFFFFFFFu - (uint32_t)(i / tb.Mmax));
+        top = pk > top ? pk : top;
+      }
+    top = block_max_u64(top, red);
+    const int a_star = (int)(0xFFFFFFFFu - (uint32_t)(top & 0xFFFFFFFFull));
+    best = 0ull;
+    for (int i = a_star * tb.Mmax + tid; i < (a_star + 1) * tb.Mmax; i += kRoundThreads) {
+      const unsigned long long c = w.cand[i];
+      best = c > best ? c : best;
+    }
+    best = block_max_u64(best, red);
   }
   const uint32_t cid = 0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull);
   const float score = __uint_as_float((uint32_t)(best >> 32));

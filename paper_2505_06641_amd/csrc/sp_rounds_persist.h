@@ -36,6 +36,8 @@ constexpr int kWinCap = 2 * kMaxBatch;          // window + look-ahead entries, 
 constexpr int kPersistRounds = 64;              // rounds per launch (ring depth)
 constexpr int kSpinLimit = 1 << 20;             // polls before a wait is given up (about a second)
 constexpr uint32_t kGenMask = 0x7FFFFFu;        // generation bits carried in a slot's first word
+constexpr int kMaxPairs = 1024;                 // (application, variant) pairs the reducer can hold
+constexpr int kSlotsPerThread = kMaxPairs / kRoundThreads;
 static_assert(kWinCap <= kRoundThreads, "one window entry per thread");
 
 struct Persist {
@@ -44,7 +46,7 @@ struct Persist {
   int32_t n_pairs;
   int32_t n_rounds;             // rounds this launch may run (<= kPersistRounds)
   uint32_t gen_base;            // generations used by earlier launches
-  unsigned long long* slots;    // [2 (parity), n_pairs, 4 (word; the last one unused)]
+  unsigned long long* slots;    // [2 (parity), n_pairs, 4 (word)]
   unsigned long long* decision; // [2 (parity), 4 (word)]: latency bits << 32 | gen; (candidate id + 1, 0 = none)
                                 //   << 32 | gen; swap-in cost bits << 32 | gen; unused
   unsigned long long* ring;     // [kPersistRounds, A, B]: generation << 32 | service position
@@ -62,6 +64,7 @@ __device__ __forceinline__ void st_dev(unsigned long long* p, unsigned long long
 // slot word 0: score bits << 32 | generation (23 bits) << 9 | valid << 8 | (b - 1)
 // slot word 1: latency bits of the candidate (float) << 32 | generation (32 bits)
 // slot word 2: swap-in cost the pair would pay in this round (float bits) << 32 | generation (32 bits)
+// slot word 3: group priority of the pair's application (eq. 14; float bits) << 32 | generation (32 bits)
 __device__ __forceinline__ unsigned long long slot_word0(float score, uint32_t gen, bool valid, int b) {
   return ((unsigned long long)__float_as_uint(score) << 32) | ((unsigned long long)(gen & kGenMask) << 9) |
          (valid ? 0x100ull : 0ull) | (unsigned long long)((b - 1) & 0xff);
@@ -148,31 +151,54 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
     const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
     unsigned long long mine = 0ull;
     float mine_lat = 0.f, mine_swap = 0.f;
-    for (int i = tid; i < ps.n_pairs; i += kRoundThreads) {
+    // with the group-first rule the slots are read once and compared twice: group priorities, then the
+    // candidates of the winning application (a thread holds at most kSlotsPerThread slots)
+    unsigned long long held[kSlotsPerThread];
+    float held_lat[kSlotsPerThread], held_swap[kSlotsPerThread];
+    unsigned long long top = 0ull;
+#pragma unroll
+    for (int q = 0; q < kSlotsPerThread; ++q) {
+      held[q] = 0ull;
+      const int i = tid + q * kRoundThreads;
+      if (i >= ps.n_pairs) continue;
       const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + i) * 4;
-      unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull;
+      unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull, v3 = 0ull;
       bool ok = false;
       for (int k = 0; k < kSpinLimit; ++k) {
         v0 = ld_dev(slot);
         v1 = ld_dev(slot + 1);
         v2 = ld_dev(slot + 2);
+        v3 = ld_dev(slot + 3);
         ok = ((uint32_t)(v0 >> 9) & kGenMask) == (gen & kGenMask) && (uint32_t)(v1 & 0xFFFFFFFFull) == gen &&
-             (uint32_t)(v2 & 0xFFFFFFFFull) == gen;
+             (uint32_t)(v2 & 0xFFFFFFFFull) == gen && (uint32_t)(v3 & 0xFFFFFFFFull) == gen;
         if (ok) break;
         __builtin_amdgcn_s_sleep(1);
       }
       if (!ok) {
         *timed_out = 1;
       } else if (v0 & 0x100ull) {
-        const int pa = i == tid ? my_a : ps.pair_app[i], pm = i == tid ? my_m : ps.pair_model[i];
+        const int pa = q == 0 ? my_a : ps.pair_app[i], pm = q == 0 ? my_m : ps.pair_model[i];
         const uint32_t cid = (uint32_t)((pa * tb.Mmax + pm) * B) + (uint32_t)(v0 & 0xffull);
         const unsigned long long pk = pack_candidate(__uint_as_float((uint32_t)(v0 >> 32)), cid);
-        if (pk > mine) {
-          mine = pk;
-          mine_lat = __uint_as_float((uint32_t)(v1 >> 32));
-          mine_swap = __uint_as_float((uint32_t)(v2 >> 32));
-        }
+        held[q] = pk;
+        held_lat[q] = __uint_as_float((uint32_t)(v1 >> 32));
+        held_swap[q] = __uint_as_float((uint32_t)(v2 >> 32));
+        const unsigned long long pt = ((unsigned long long)ordered_bits(__uint_as_float((uint32_t)(v3 >> 32))) << 32) |
+                                      (unsigned long long)(0xFFFFFFFFu - (uint32_t)pa);
+        top = pt > top ? pt : top;
       }
+    }
+    int a_star = -1;                                           // -1: every application competes
+    if (tb.pol_group_first) {
+      top = block_max_u64(top, red);
+      if (top != 0ull) a_star = (int)(0xFFFFFFFFu - (uint32_t)(top & 0xFFFFFFFFull));
+    }
+#pragma unroll
+    for (int q = 0; q < kSlotsPerThread; ++q) {
+      if (held[q] == 0ull) continue;
+      const uint32_t cid = 0xFFFFFFFFu - (uint32_t)(held[q] & 0xFFFFFFFFull);
+      if (a_star >= 0 && (int)(cid / (uint32_t)B) / tb.Mmax != a_star) continue;
+      if (held[q] > mine) { mine = held[q]; mine_lat = held_lat[q]; mine_swap = held_swap[q]; }
     }
     const unsigned long long all = block_max_u64(mine, red);
     if (all != 0ull && mine == all) {                         // candidate ids are unique: one writer
@@ -201,6 +227,7 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
 __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables tb, Window w, Persist ps) {
   __shared__ int32_t win[kWinCap];
   __shared__ float4 ent[kWinCap];
+  __shared__ float om[kWinCap];              // ordering value of each entry (for the group priority)
   __shared__ float lat_s[kMaxBatch];
   __shared__ int32_t wave_cnt[kRoundThreads / 64], keep_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
@@ -218,7 +245,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int pair = blockIdx.x;
   const int a = ps.pair_app[pair], m = ps.pair_model[pair];
-  const int B = tb.B, cap = kWinCap;
+  const int B = tb.B, Bw = tb.Bcap, cap = kWinCap;   // B: row stride of the tables; Bw: largest batch
   const int kind = tb.penalty[a];
   const float lmin = tb.lmin[a];
   const float my_swap = tb.swap[a * tb.Mmax + m];
@@ -241,7 +268,8 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
       const bool has = tid < nb;
       int pos = 0;
       float4 e = make_float4(0.f, 1.f, 0.f, 0.f);
-      if (has) { pos = win[tid]; e = ent[tid]; }
+      float ov = 0.f;
+      if (has) { pos = win[tid]; e = ent[tid]; ov = om[tid]; }
       const bool keep = has && tid >= shift && !is_dead(kind, e.y, E0);
       const unsigned long long bal = __ballot(keep);
       if (lane == 0) keep_cnt[wave] = __popcll(bal);
@@ -254,7 +282,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
       }
       if (total != nb) {
         before += __popcll(bal & ((1ull << lane) - 1ull));
-        if (keep) { win[before] = pos; ent[before] = e; }
+        if (keep) { win[before] = pos; ent[before] = e; om[before] = ov; }
         nb = total;
       }
       shift = 0;
@@ -314,13 +342,16 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
           nb = total;
         }
       }
-      for (int j = nb_old + tid; j < nb; j += kRoundThreads) ent[j] = window_entry(tb, w, win[j], m);
+      for (int j = nb_old + tid; j < nb; j += kRoundThreads) {
+        ent[j] = window_entry(tb, w, win[j], m);
+        om[j] = ordering_value(tb, w, win[j]);
+      }
       __syncthreads();
     };
 
     // ---- fewer than B entries left: the round has to wait for the walk ----
-    if (nb < B && scan_end < seg_e) walk(1 << 30, 1);
-    const int nbe = min(nb, B);
+    if (nb < Bw && scan_end < seg_e) walk(1 << 30, 1);
+    const int nbe = min(nb, Bw);
 
     // ---- the window's positions for the commit workgroup ----
     if (m == 0 && tid < nbe)
@@ -330,7 +361,13 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
     unsigned long long best = 0ull;
     const float swap_now = (prev_a == a && prev_m == m) ? 0.f : my_swap;
     if (nbe > 0)
-      best = triangle_best(kind, ent, lat_s, nbe, B, t + (double)swap_now, (uint32_t)((a * tb.Mmax + m) * B), nullptr);
+      best = triangle_best(scoring_penalty(tb, kind), ent, lat_s, nbe, Bw, t + (double)swap_now,
+                           (uint32_t)((a * tb.Mmax + m) * B), nullptr, tb.pol_whole ? nbe : 0);
+    float prio = 0.f;
+    if (tb.pol_group_first) {          // eq. (14) over the window, the same fixed-order sum as in k_round_score
+      const double psum = block_sum_f64(tid < nbe ? (double)om[tid] : 0.0, dsum);
+      prio = nbe > 0 ? (float)(psum / (double)nbe) : 0.f;
+    }
     best = block_max_u64(best, red);
 
     // ---- publish this pair's best candidate ----
@@ -338,6 +375,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
       unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + pair) * 4;
       const bool valid = best != 0ull;
       const int b = valid ? (int)((0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull)) % (uint32_t)B) + 1 : 1;
+      st_dev(slot + 3, ((unsigned long long)__float_as_uint(prio) << 32) | (unsigned long long)gen);
       st_dev(slot + 2, ((unsigned long long)__float_as_uint(swap_now) << 32) | (unsigned long long)gen);
       st_dev(slot + 1, ((unsigned long long)__float_as_uint(lat_s[b - 1]) << 32) | (unsigned long long)gen);
       st_dev(slot, slot_word0(__uint_as_float((uint32_t)(best >> 32)), gen, valid, b));
@@ -345,7 +383,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
 
     // ---- look-ahead: one step of the walk while the candidates are exchanged ----
     // (three dependent trips to memory, about twice the exchange: only once less than two windows are left)
-    if (nb < min(2 * B, cap) && scan_end < seg_e) walk(1, 4);
+    if (nb < min(2 * Bw, cap) && scan_end < seg_e) walk(1, 4);
 
     // ---- wait for the decision ----
     if (tid == 0) {

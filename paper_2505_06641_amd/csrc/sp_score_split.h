@@ -409,7 +409,7 @@ __device__ __forceinline__ void class_tiles_and_finish(
     if (err) atomicOr(&w.st->err, err);
     const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
     w.key[id] = key;
-    sortkey[pos] = ~__float_as_uint(key);
+    sortkey[pos] = tb.pol_edf ? __float_as_uint(Di) : ~__float_as_uint(key);   // ascending deadline, or descending key
     w.D_g[pos] = Di;
     w.w_g[pos] = wi;
   }

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
 // grouped arrays (local to the application's range), the key comes straight from the sorted key bits.
 __global__ void k_finish_order(int n, int n_valid_at /*index into seg*/, const int32_t* __restrict__ seg,
                                const int32_t* __restrict__ grouped_pos, const uint32_t* __restrict__ sorted_keys,
-                               const int32_t* __restrict__ ids_grouped, Window w) {
+                               const int32_t* __restrict__ ids_grouped, Window w, int edf) {
   const int pos = blockIdx.x * blockDim.x + threadIdx.x;
   if (pos >= n) return;
   const int nv = seg[n_valid_at];
@@ -229,7 +229,8 @@ __global__ void k_finish_order(int n, int n_valid_at /*index into seg*/, const i
     w.id_s[pos] = ids_grouped[gp];
     w.D_s[pos] = w.D_g[gp];
     w.w_s[pos] = w.w_g[gp];
-    w.key_s[pos] = __uint_as_float(~sorted_keys[pos]);
+    // the passes sorted the inverted key bits, or (earliest deadline first) the deadline bits
+    w.key_s[pos] = edf ? w.key[ids_grouped[gp]] : __uint_as_float(~sorted_keys[pos]);
     w.alive_s[pos] = 1;
   } else {
     w.alive_s[pos] = 0;

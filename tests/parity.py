@@ -69,9 +69,9 @@ def members_by_round(round_of, order_of, n_rounds):
     return [np.asarray(m, dtype=np.int64) for m in out]
 
 
-def replay(profile, requests, ea_ref, key_ref, log, members, done, tol):
+def replay(profile, requests, ea_ref, key_ref, log, members, done, tol, policy=None):
     """Replay the library's rounds in the oracle.  Returns (window, stats)."""
-    win = orc.Window(profile, requests, ea=ea_ref, key=key_ref)
+    win = orc.Window(profile, requests, ea=ea_ref, key=key_ref, policy=policy)
     stats = {"rounds": len(log), "exact": 0, "ties": 0, "max_score_rel": 0.0}
     for r, rec in enumerate(log):
         a, m, b = int(rec["app"]), int(rec["model"]), int(rec["batch"])
@@ -82,20 +82,27 @@ def replay(profile, requests, ea_ref, key_ref, log, members, done, tol):
         assert d is not None, f"round {r}: library committed a batch but nothing is live in the oracle"
         assert abs(rec["t_start_ms"] - win.t) <= 1e-9 * max(1.0, abs(win.t)), f"round {r}: clock {rec['t_start_ms']} vs {win.t}"
         exact = (d["app"], d["model"], d["batch"]) == (a, m, b) and np.array_equal(d["ids"], ids)
-        kind = int(profile.penalty[a])
+        kind = win.scoring_penalty(a)
         t_end = win.start_time(a, m) + win.lat[a][m, b - 1]
-        mine = float((win.key[ids] * orc.utility(win.ea[ids, m], kind, win.D[ids], t_end)).sum())
+        mine = float((win.wsum[ids] * orc.utility(win.ea[ids, m], kind, win.D[ids], t_end)).sum())
         if exact:
             stats["exact"] += 1
         else:
             live = win.live_queue(a)
             assert np.all(np.isin(ids, live)), f"round {r}: a chosen request is not live in the oracle"
-            assert mine >= d["score"] * (1.0 - tol) - 1e-300, \
+            best_here = d["score"]
+            if win.group_first and d["app"] != a:
+                # a different group went first: its priority must tie the oracle's choice within tolerance
+                pa, pb = win.group_priority(a), win.group_priority(d["app"])
+                assert pa is not None and pa >= pb - tol * abs(pb), f"round {r}: group {a} ({pa!r}) is not the top group ({pb!r})"
+                best_here = float(np.max(cube[a]))
+            assert mine >= best_here * (1.0 - tol) - 1e-300, \
                 f"round {r}: library chose ({a},{m},{b}) worth {mine!r}, oracle best {d['score']!r} at " \
                 f"({d['app']},{d['model']},{d['batch']})"
             others = live[~np.isin(live, ids)]
             if others.size:
-                assert win.key[others].max() <= win.key[ids].min() * (1.0 + tol), \
+                lowest = float(win.omega[ids].min())
+                assert win.omega[others].max() <= lowest + tol * abs(lowest), \
                     f"round {r}: batch is not a top-{b} prefix within key tolerance"
             stats["ties"] += 1
         e = float(rel_err(rec["score"], mine))

@@ -27,14 +27,14 @@ def gpu():
     return torch, binding
 
 
-def run_window(gpu, w, max_rounds, ctx=None, want_cube=False):
+def run_window(gpu, w, max_rounds, ctx=None, want_cube=False, policy=None):
     """Score + schedule one workload through the C ABI; everything back on the host."""
     torch, binding = gpu
     p, rq = w.profile, w.requests
     n = rq.n
     own = ctx is None
     if own:
-        ctx = binding.Context(p, max(n, 1))
+        ctx = binding.Context(p, max(n, 1), policy=policy)
     x, app, D, wt = binding.to_device(rq)
     ea = torch.full((n, ctx.m_max), -7.0, device="cuda:0")
     key = torch.full((n,), -7.0, device="cuda:0")
@@ -62,22 +62,25 @@ def run_window(gpu, w, max_rounds, ctx=None, want_cube=False):
     return out
 
 
-def full_parity(gpu, w, max_rounds, tol=TOL, ea_tol=None, want_cube=False):
+def full_parity(gpu, w, max_rounds, tol=TOL, ea_tol=None, want_cube=False, policy=None):
     torch, binding = gpu
     p, rq = w.profile, w.requests
     ea_ref, key_ref = orc.score_requests(p, rq)
-    got = run_window(gpu, w, max_rounds, want_cube=want_cube)
+    got = run_window(gpu, w, max_rounds, want_cube=want_cube, policy=policy)
     stats = {}
     stats["ea_rel"] = parity.assert_close("EA", got["ea"], ea_ref, ea_tol or tol)
     stats["key_rel"] = parity.assert_close("key", got["key"], key_ref, ea_tol or tol, floor=1e-30)
-    stats["order_swaps"] = parity.check_order(got["order"], got["seg"], rq.app, key_ref, p.n_apps, tol)
+    edf = policy is not None and policy.order == wl.ORDER_EDF
+    stats["order_swaps"] = parity.check_order(got["order"], got["seg"], rq.app,
+                                              -orc.widen(rq.deadline_rel_ms) if edf else key_ref, p.n_apps, tol)
     if want_cube:
-        ref_cube = orc.Window(p, rq, ea=ea_ref, key=key_ref).score_cube()
+        ref_cube = orc.Window(p, rq, ea=ea_ref, key=key_ref, policy=policy).score_cube()
         valid = np.isfinite(ref_cube)
         assert np.array_equal(got["cube"] >= 0, valid), "candidate sets differ"
         stats["cube_rel"] = parity.assert_close("score cube", got["cube"][valid], ref_cube[valid], tol, floor=1e-12)
     members = parity.members_by_round(got["round_of"], got["order_of"], len(got["log"]))
-    win, rstats = parity.replay(p, rq, ea_ref, key_ref, got["log"], members, got["summary"]["done"] == 1, tol)
+    win, rstats = parity.replay(p, rq, ea_ref, key_ref, got["log"], members, got["summary"]["done"] == 1, tol,
+                                policy=policy)
     stats.update(rstats)
     stats["util_rel"] = parity.check_outputs(win, got["model"], got["round_of"], got["order_of"], got["util"],
                                              got["summary"], tol)
@@ -301,6 +304,45 @@ def test_round_by_round_equals_schedule_and_is_deterministic(gpu):
     assert rc == binding.SP_DONE and log2 == a["log"] and s2 == a["summary"]
     a["close"]()
     b["close"]()
+
+
+@pytest.mark.parametrize("name", ["alg1", "lo_priority", "lo_edf", "maxacc_edf", "edf_batched", "capped"])
+def test_policies_of_the_evaluation_on_both_round_paths(gpu, name):
+    """Sec. 6.1 "Baselines and Metrics" and Alg. 1 as printed, as knobs on the same kernels."""
+    torch, binding = gpu
+    policy = {"edf_batched": wl.Policy(order=wl.ORDER_EDF, weight=wl.WEIGHT_UNIT),
+              "capped": wl.Policy(batch_cap=5, choice=wl.CHOICE_MAX_ACCURACY)}.get(name) or wl.named_policy(name)
+    n = 600 if policy.batch_cap == 1 else 2400
+    w = wl.tiny(seed=97, n=n, classes=(5, 3, 40, 2), models=(3, 2, 8, 5), max_batch=19, feat_dim=19,
+                penalty=wl.PEN_LINEAR, deadline=(6.0, 150.0), fractions=(0.4, 0.1, 0.3, 0.2))
+    w.profile.penalty[:] = [wl.PEN_LINEAR, wl.PEN_STEP, wl.PEN_SIGMOID, wl.PEN_LINEAR]
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True, policy=policy)      # rounds in one launch
+    assert got["summary"]["done"] == 1 and stats["rounds"] > 10
+    if policy.batch_cap:
+        assert max(r["batch"] for r in got["log"]) <= policy.batch_cap
+    # the same window one round per call (two kernels per round)
+    ctx = binding.Context(w.profile, n, policy=policy)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_score(x, app, D, wt)
+    for rec in got["log"]:
+        rc, dec = ctx.sp_greedy_round()
+        assert rc == binding.SP_OK and dec == rec
+    assert ctx.sp_greedy_round()[0] == binding.SP_DONE
+    # back to the default policy: the window has to be scored again, and then runs as without a policy
+    ctx.sp_set_policy(None)
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_schedule(0)
+    assert e.value.status == binding.SP_ESTATE
+    ctx.sp_score(x, app, D, wt)
+    rc, summ, log = ctx.sp_schedule(0, log_capacity=4096)
+    plain = run_window(gpu, w, 0)
+    assert log == plain["log"] and summ == plain["summary"]
+    plain["close"]()
+    bad = wl.Policy(order=7)
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_set_policy(bad)
+    assert e.value.status == binding.SP_EINVAL
+    ctx.close()
 
 
 @pytest.mark.parametrize("kind", [wl.PEN_STEP, wl.PEN_LINEAR, wl.PEN_SIGMOID])
