@@ -65,7 +65,7 @@ def scoring_flops_per_request(p, a):
     return head + 2 * C * M
 
 
-def cpu_baseline(w, n_sample, rounds):
+def cpu_baseline(w, n_sample, rounds, policy=None):
     """The oracle, as it stands, on the first n_sample requests of the same workload."""
     from oracle import sneakpeek_oracle as orc
     from paper_2505_06641_amd import workloads as wl
@@ -80,7 +80,7 @@ def cpu_baseline(w, n_sample, rounds):
     t0 = time.perf_counter()
     ea, key = orc.score_requests(w.profile, sub)
     t1 = time.perf_counter()
-    win = orc.Window(w.profile, sub, ea=ea, key=key)
+    win = orc.Window(w.profile, sub, ea=ea, key=key, policy=policy)
     win.run(max_rounds=rounds)
     t2 = time.perf_counter()
     p = w.profile
@@ -99,6 +99,11 @@ def main():
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0)
+    ap.add_argument("--policy", default="sneakpeek",
+                    choices=["sneakpeek", "alg1", "lo_priority", "lo_edf", "maxacc_edf"],
+                    help="scheduling policy (Sec. 6.1 baselines, Alg. 1 as printed); default: the joint arg max")
+    ap.add_argument("--priors", action="store_true", help="Dirichlet priors of the three kinds of Sec. 6.3 on the applications")
+    ap.add_argument("--swap-costs", action="store_true", help="swap-in cost of 0.5-8 ms per variant")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the steps, run one elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB): "
                          "the known-size kernel that hardware byte counters of a profiler run are scaled by")
@@ -119,7 +124,12 @@ def main():
     n, A = rq.n, int(p.n_apps)
     m_max, B = int(np.max(p.n_models)), int(p.max_batch)
     rounds = w.rounds                      # <= 0: until the queue is exhausted
-    ctx = binding.Context(p, n)
+    if args.priors:
+        wl.attach_priors(p, seed=1000 + w.seed)
+    if args.swap_costs:
+        wl.attach_swap_costs(p, seed=2000 + w.seed)
+    policy = None if args.policy == "sneakpeek" else wl.named_policy(args.policy)
+    ctx = binding.Context(p, n, policy=policy)
     x, app, D, wt = binding.to_device(rq)
     model = torch.empty(n, dtype=torch.int32, device="cuda:0")
     rnd = torch.empty(n, dtype=torch.int32, device="cuda:0")
@@ -200,7 +210,8 @@ def main():
         "config": {"workload": f"{w.name}: {A} applications, C={int(np.max(p.n_classes))}, M={m_max}, B={B}, "
                                f"N={n}, d={int(p.feat_dim)}, H={int(p.hidden_dim)}, seed {w.seed}; "
                                f"one scoring pass + {'greedy rounds until exhausted' if rounds <= 0 else str(rounds) + ' greedy rounds'}",
-                   "n_requests": n, "rounds_run": n_rounds,
+                   "n_requests": n, "rounds_run": n_rounds, "policy": args.policy, "priors": bool(args.priors),
+                   "swap_costs": bool(args.swap_costs),
                    "rounds_path": "one launch" if ctx.rounds_in_one_launch else "two kernels per round"},
         "greedy_round_latency_us": {"mean": float(np.mean(per_round)) if per_round else None,
                                     "p50": float(np.percentile(per_round, 50)) if per_round else None,
@@ -213,7 +224,7 @@ def main():
     if not args.no_cpu_baseline:
         default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 16384, "cfg5": 131072}[args.workload]
         ns = min(n, args.cpu_sample or default_sample)
-        out["cpu_baseline"] = cpu_baseline(w, ns, rounds)
+        out["cpu_baseline"] = cpu_baseline(w, ns, rounds, policy)
     ctx.close()
     print(json.dumps(out))
 
