@@ -173,11 +173,11 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
 #pragma unroll
   for (int hb = 0; hb < kMlpH / 32; ++hb) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      _Float16 hi, lo;
-      split_f16(hacc[hb][v] * hs, hi, lo);
-      xh[2 * hb + (v >> 3)][v & 7] = hi;
-      xl[2 * hb + (v >> 3)][v & 7] = lo;
+    for (int v = 0; v < 16; v += 2) {
+      f16x2 hi, lo;
+      split_f16x2(hacc[hb][v] * hs, hacc[hb][v + 1] * hs, hi, lo);
+      xh[2 * hb + (v >> 3)][v & 7] = hi[0]; xh[2 * hb + (v >> 3)][(v & 7) + 1] = hi[1];
+      xl[2 * hb + (v >> 3)][v & 7] = lo[0]; xl[2 * hb + (v >> 3)][(v & 7) + 1] = lo[1];
     }
   }
 

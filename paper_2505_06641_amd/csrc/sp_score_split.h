@@ -194,6 +194,22 @@ __device__ __forceinline__ void split_f16(float v, _Float16& hi, _Float16& lo) {
   hi = (_Float16)v;
   lo = (_Float16)(v - (float)hi);
 }
+// The same for two values at once, written so that the conversions pair up (one packed conversion for
+// the two hi parts, one for the two lo parts) and the remainder is a single fused operation on the
+// half-precision value: 2 instructions per value instead of 4.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split_f16x2(float a, float b, f16x2& hi, f16x2& lo) {
+  const f32x2 v = {a, b};
+  hi = __builtin_convertvector(v, f16x2);
+  // remainder v - hi with the half-precision operand read straight out of the packed register
+  // (mixed-precision fma: op_sel_hi marks source 0 as fp16, op_sel picks its upper half)
+  const uint32_t hb = __builtin_bit_cast(uint32_t, hi);
+  f32x2 r;
+  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r[0]) : "v"(hb), "v"(a));
+  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r[1]) : "v"(hb), "v"(b));
+  lo = __builtin_convertvector(r, f16x2);
+}
 
 // Matrix phase of one class tile: acc = (W' x') for the tile's 32 classes and the wavefront's 32 requests.
 template <int D>
@@ -256,6 +272,10 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
                                               int ct, int C, int g, int lane, bool valid, int64_t dump_row,
                                               float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
+  // The other wavefront of this SIMD is, most of the time, streaming the MFMAs of its matrix phase and
+  // always has the next one ready; without a higher priority the few MFMAs of this phase would wait
+  // for that whole stream to end.
+  __builtin_amdgcn_s_setprio(2);
   float4 bq[4];
   {
     const float4* bp = blk + SB::kWUnits + SB::kTabUnits;
@@ -285,26 +305,30 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
   m2 = m2n;
   const float shift = kExpShift - m2n;
-  f16x8 ph[2], pl[2];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], kLog2e, shift));   // in (0, 2^14]
-    _Float16 hi, lo;
-    split_f16(p, hi, lo);
-    ph[v >> 3][v & 7] = hi;
-    pl[v >> 3][v & 7] = lo;
-    eacc[v] *= scale;
-  }
-  // exponentials x table tile (accuracies and the row of ones)
+  for (int v = 0; v < 16; ++v) eacc[v] *= scale;
+  // exponentials x table tile (accuracies and the row of ones), eight classes per lane at a time so that
+  // the first MFMAs are under way while the second half is still being exponentiated
   const float4* tp = blk + SB::kWUnits + lane;
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
+    f16x8 ph, pl;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[8 * ks + e], kLog2e, shift));       // in (0, 2^14]
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[8 * ks + e + 1], kLog2e, shift));
+      f16x2 hi, lo;
+      split_f16x2(p0, p1, hi, lo);
+      ph[e] = hi[0]; ph[e + 1] = hi[1];
+      pl[e] = lo[0]; pl[e + 1] = lo[1];
+    }
     const f16x8 th = as_f16x8(tp[(ks * 2 + 0) * 64]);
     const f16x8 tl = as_f16x8(tp[(ks * 2 + 1) * 64]);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, ph[ks], eacc, 0, 0, 0);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, ph[ks], eacc, 0, 0, 0);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, pl[ks], eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, ph, eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, ph, eacc, 0, 0, 0);
+    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, pl, eacc, 0, 0, 0);
   }
+  __builtin_amdgcn_s_setprio(0);
 }
 
 // Class tiles and epilogue shared by the scoring kernels: given the wavefront's 32 requests as split
@@ -328,46 +352,54 @@ __device__ __forceinline__ void class_tiles_and_finish(
   for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
   const int64_t dump_row = (int64_t)id * tb.Cmax;
 
-  // The two wavefronts that share a SIMD run half a tile apart: wavefronts 0..3 do the matrix phase of
-  // tile t while wavefronts 4..7 do the softmax phase of tile t-1, then they swap, so the matrix cores
-  // and the vector ALU of every SIMD are busy at the same time.  Block t+1 is fetched into the third
-  // buffer in two halves, one per phase.
+  // The class tiles are software-pipelined inside every wavefront: an iteration holds the matrix phase
+  // of tile t+1 and the softmax phase of tile t, which do not depend on each other, and the two
+  // wavefronts that share a SIMD take them in opposite order (wavefronts 0..3 matrix phase first,
+  // 4..7 softmax phase first), so that the matrix cores always have a wavefront feeding them while the
+  // other one keeps the vector ALU busy.  One barrier per tile: block t+2 is fetched through registers
+  // in two halves during the iteration and is complete in LDS at its end.
   const bool late = wave >= kMfWaves / 2;
-  f32x16 acc;
-#define SP_TILE(T, CUR, NXT, PRV)                                                                              \
-  if ((T) < CT) {                                                                                              \
-    const bool more = (T) + 1 < CT;                                                                            \
-    const float4* nsrc = src + (size_t)(more ? (T) + 1 : (T)) * SB::kUnits;                                    \
-    stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
-    if (!late) {                                                                                               \
-      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
-    } else if ((T) > 0) {                                                                                      \
-      softmax_phase<D, DUMP>(PRV, acc, unscale, eacc, m2, (T) - 1, C, g, lane, valid, dump_row, logits_out);   \
-    }                                                                                                          \
-    stage_park<D, 0>(NXT, stg, tid);      /* (after the last tile: a copy nobody reads) */                     \
-    __builtin_amdgcn_s_barrier();          /* phase boundary: nothing read in the next phase was written here */ \
-    stage_fetch<D, 1>(nsrc, stg, tid);                                                                         \
-    if (!late) {                                                                                               \
-      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
-    } else {                                                                                                   \
-      logits_phase<D>(CUR, xh, xl, acc, lane);                                                                 \
-    }                                                                                                          \
-    stage_park<D, 1>(NXT, stg, tid);                                                                           \
-    __syncthreads();                       /* block T+1 is complete in LDS */                                  \
-  }
+  f32x16 acc, accn;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) accn[v] = 0.f;
   StageRegs<D> stg;
   stg.v[0] = stg.v[1] = stg.v[2] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // block 1 has to be in LDS before the first iteration reads it
+  {
+    const float4* nsrc = src + (size_t)(CT > 1 ? 1 : 0) * SB::kUnits;
+    stage_fetch<D, 0>(nsrc, stg, tid);
+    logits_phase<D>(buf_a, xh, xl, acc, lane);
+    stage_park<D, 0>(buf_b, stg, tid);
+    stage_fetch<D, 1>(nsrc, stg, tid);
+    stage_park<D, 1>(buf_b, stg, tid);
+    __syncthreads();
+  }
+#define SP_TILE(T, CUR, NXT, FILL)                                                                             \
+  if ((T) < CT) {                                                                                              \
+    const bool more = (T) + 1 < CT;                                                                            \
+    const float4* nsrc = src + (size_t)((T) + 2 < CT ? (T) + 2 : CT - 1) * SB::kUnits;                        \
+    stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
+    if (!late) {                                                                                               \
+      if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
+      stage_park<D, 0>(FILL, stg, tid);   /* (past the last block: a copy nobody reads) */                     \
+      stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
+      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+    } else {                                                                                                   \
+      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+      stage_park<D, 0>(FILL, stg, tid);                                                                        \
+      stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
+      if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
+    }                                                                                                          \
+    stage_park<D, 1>(FILL, stg, tid);                                                                          \
+    acc = accn;                                                                                                \
+    __syncthreads();                       /* block T+2 is complete in LDS, blocks T and T+1 are free */       \
+  }
   for (int t0 = 0; t0 < CT; t0 += 3) {
     SP_TILE(t0, buf_a, buf_b, buf_c)
     SP_TILE(t0 + 1, buf_b, buf_c, buf_a)
     SP_TILE(t0 + 2, buf_c, buf_a, buf_b)
   }
 #undef SP_TILE
-  if (late) {
-    const int last = (CT - 1) % 3;
-    const float4* lb = last == 0 ? buf_a : (last == 1 ? buf_b : buf_c);
-    softmax_phase<D, DUMP>(lb, acc, unscale, eacc, m2, CT - 1, C, g, lane, valid, dump_row, logits_out);
-  }
   if (DUMP) return;
 
   // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
@@ -506,11 +538,11 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     const float xs = __uint_as_float((uint32_t)(127 + ex) << 23);
     unscale = __uint_as_float((uint32_t)(127 - ex) << 23) * w_unscale[a];
 #pragma unroll
-    for (int q = 0; q < D / 2; ++q) {
-      _Float16 hi, lo;
-      split_f16(xr[q] * xs, hi, lo);
-      xh[q >> 3][q & 7] = hi;
-      xl[q >> 3][q & 7] = lo;
+    for (int q = 0; q < D / 2; q += 2) {
+      f16x2 hi, lo;
+      split_f16x2(xr[q] * xs, xr[q + 1] * xs, hi, lo);
+      xh[q >> 3][q & 7] = hi[0]; xh[q >> 3][(q & 7) + 1] = hi[1];
+      xl[q >> 3][q & 7] = lo[0]; xl[q >> 3][(q & 7) + 1] = lo[1];
     }
   }
   class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
