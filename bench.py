@@ -36,6 +36,8 @@ PEAK_VALU_F32_TFLOPS = 157.3
 KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
 MEASURED_TRAFFIC = {
     # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
+    "cfg5": (1523.20e6 + 110.17e6, "934227ee05d9e09345229dee6ef446bd87b334ca538ee053734df315ab7f2af6"),
+    "cfg4": (95.01e6 + 3.20e6, "934227ee05d9e09345229dee6ef446bd87b334ca538ee053734df315ab7f2af6"),
 }
 
 
