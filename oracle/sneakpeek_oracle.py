@@ -20,6 +20,7 @@ What each function follows:
 * service_order            -- Alg. 1 ("requests in g sorted by priority").
 * Window.*                 -- Alg. 1 generalised to batch-capped greedy rounds;
   eq. (1) clock with the batch as the unit; eq. (13) arg max.
+* split_labels             -- Sec. 5.3.2, data-aware subgroups of an application.
 * dirichlet_posterior_mean -- Sec. 4.2, eq. (10)-(11).
 * smoothed_posterior       -- Sec. 4.2, eq. (10)-(11) with the head's output as
   soft evidence (y = k * theta) under a per-application prior.
@@ -211,6 +212,18 @@ def score_requests(profile, requests, chunk=16384, return_theta=False):
     return ea, key
 
 
+def split_labels(thetas, threshold=0.5):
+    """Sec. 5.3.2 "Enhancements for Grouped Scheduling": a request joins the subgroup of the class its
+    SneakPeek probabilities point to (theta_c > 1/2, so at most one class qualifies); with no such class
+    it stays in the application's unsplit group.  Returns 1 + class, or 0, per request."""
+    out = np.zeros(len(thetas), dtype=np.int64)
+    for i, th in enumerate(thetas):
+        th = np.asarray(th, dtype=np.float64)
+        c = int(np.argmax(th))
+        out[i] = 1 + c if th[c] > threshold else 0
+    return out
+
+
 def service_order(app, key, n_apps):
     """Per application, request ids by (key descending, id ascending).  Earliest deadline first is this
     with the negated deadline as the key."""
@@ -228,7 +241,7 @@ class Window:
     """State of one scheduling window: who is still pending, the worker clock
     t (ms since the window's start), and what has been assigned so far."""
 
-    def __init__(self, profile, requests, ea=None, key=None, policy=None):
+    def __init__(self, profile, requests, ea=None, key=None, policy=None, sub=None):
         self.p = profile
         self.n = int(requests.app.shape[0])
         self.app = np.asarray(requests.app)
@@ -246,8 +259,20 @@ class Window:
         self.B = min(int(profile.max_batch), cap) if cap > 0 else int(profile.max_batch)
         # what orders requests inside an application, and what a group's priority averages (eq. 14)
         self.omega = -self.D if self.edf else self.key
-        self.order = service_order(self.app, self.omega, profile.n_apps)
         self.wsum = np.ones(self.n) if self.unit_weight else self.key
+        # groups: the applications, or (Sec. 5.3.2) every non-empty (application, subgroup) pair in
+        # ascending order; everything below that takes a group index g looks its tables up through gapp
+        if g("split_groups") == 1:
+            assert sub is not None, "group splitting needs the subgroup label of every request (split_labels)"
+            pairs = sorted(set(zip(self.app.tolist(), np.asarray(sub).tolist())))
+            index = {pr: i for i, pr in enumerate(pairs)}
+            self.gapp = [int(pr[0]) for pr in pairs]
+            self.gid = np.array([index[(int(a), int(sb))] for a, sb in zip(self.app, np.asarray(sub))], dtype=np.int64)
+        else:
+            self.gapp = list(range(int(profile.n_apps)))
+            self.gid = self.app.astype(np.int64)
+        self.G = len(self.gapp)
+        self.order = service_order(self.gid, self.omega, self.G)
         self.lat = [widen(l) for l in profile.lat_ms]
         self.lmin = [float(l[:, 0].min()) for l in self.lat]
         # cost of bringing a variant in (Sec. 3.1: latency "including any context switch time"; Sec. 5.2:
@@ -268,24 +293,25 @@ class Window:
         self.log = []
 
     # -- who can still be served -------------------------------------------
-    def live_queue(self, a):
-        """Live requests of application a in service order."""
-        ids = self.order[a]
+    def live_queue(self, g):
+        """Live requests of group g (an application, or one of its subgroups) in service order."""
+        a = self.gapp[g]
+        ids = self.order[g]
         ids = ids[self.alive[ids]]
         dead = is_dead(int(self.p.penalty[a]), self.D[ids], self.t + self.lmin[a])
         return ids[~dead]
 
-    def candidate_window(self, a):
-        return self.live_queue(a)[: self.B]
+    def candidate_window(self, g):
+        return self.live_queue(g)[: self.B]
 
     def scoring_penalty(self, a):
         """Penalty kind the candidates are compared under: the application's own (eq. 13), or the step
         penalty when variants are compared by accuracy among those that meet the deadline."""
         return PEN_STEP if self.max_accuracy else int(self.p.penalty[a])
 
-    def group_priority(self, a):
-        """eq. (14) over the application's candidate window; None when it is empty."""
-        q = self.candidate_window(a)
+    def group_priority(self, g):
+        """eq. (14) over the group's candidate window; None when it is empty."""
+        q = self.candidate_window(g)
         return None if q.shape[0] == 0 else float(np.mean(self.omega[q]))
 
     def start_time(self, a, m):
@@ -299,11 +325,12 @@ class Window:
     def score_cube(self):
         """Score[a, m, b-1] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
         over the first b live requests of a; -inf where (a,m,b) is not a candidate."""
-        A, B = int(self.p.n_apps), int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
+        G, B = self.G, int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
         m_max = int(np.max(self.p.n_models))
-        cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
-        for a in range(A):
-            q = self.candidate_window(a)
+        cube = np.full((G, m_max, B), -np.inf, dtype=np.float64)
+        for g in range(G):
+            a = self.gapp[g]
+            q = self.candidate_window(g)
             nb = q.shape[0]
             if nb == 0:
                 continue
@@ -315,18 +342,19 @@ class Window:
                     e = self.start_time(a, m) + self.lat[a][m, b - 1]
                     members = q[:b]
                     terms = self.wsum[members] * utility(self.ea[members, m], kind, self.D[members], e)
-                    cube[a, m, b - 1] = terms.sum()
+                    cube[g, m, b - 1] = terms.sum()
         return cube
 
     def score_cube_fast(self):
         """Same numbers as score_cube with the (b, j) triangle done as one
         masked array per (a, m); kept beside the loop version so that a test
         can check one against the other."""
-        A, B = int(self.p.n_apps), int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
+        G, B = self.G, int(self.p.max_batch)     # the cube keeps the profile's width; sizes above the cap stay -inf
         m_max = int(np.max(self.p.n_models))
-        cube = np.full((A, m_max, B), -np.inf, dtype=np.float64)
-        for a in range(A):
-            q = self.candidate_window(a)
+        cube = np.full((G, m_max, B), -np.inf, dtype=np.float64)
+        for g in range(G):
+            a = self.gapp[g]
+            q = self.candidate_window(g)
             nb = q.shape[0]
             if nb == 0:
                 continue
@@ -336,9 +364,9 @@ class Window:
                 e = self.start_time(a, m) + self.lat[a][m, :nb]    # [b]
                 u = utility(self.ea[q, m][None, :], kind, self.D[q][None, :], e[:, None])
                 terms = np.where(tri, self.wsum[q][None, :] * u, 0.0)
-                cube[a, m, :nb] = terms.sum(axis=1)
+                cube[g, m, :nb] = terms.sum(axis=1)
                 if self.whole:
-                    cube[a, m, : nb - 1] = -np.inf
+                    cube[g, m, : nb - 1] = -np.inf
         return cube
 
     def decide(self, cube=None):
@@ -351,19 +379,20 @@ class Window:
         if self.group_first:
             # Alg. 1: the group with the highest mean priority goes first (ties: smallest application),
             # then the variant (and batch size) is chosen for that group alone
-            prio = [self.group_priority(a) for a in range(cube.shape[0])]
+            prio = [self.group_priority(g) for g in range(cube.shape[0])]
             best = max(v for v in prio if v is not None)
-            a_star = min(a for a, v in enumerate(prio) if v is not None and v == best)
+            g_star = min(g for g, v in enumerate(prio) if v is not None and v == best)
             masked = np.full_like(cube, -np.inf)
-            masked[a_star] = cube[a_star]
+            masked[g_star] = cube[g_star]
             cube = masked
-        flat = int(np.argmax(cube))            # first maximum in C order = smallest (a,m,b)
-        a, m, bi = np.unravel_index(flat, cube.shape)
+        flat = int(np.argmax(cube))            # first maximum in C order = smallest (group, m, b)
+        g, m, bi = np.unravel_index(flat, cube.shape)
         b = int(bi) + 1
-        ids = self.candidate_window(int(a))[:b]
-        return {"app": int(a), "model": int(m), "batch": b, "score": float(cube[a, m, bi]),
+        a = self.gapp[int(g)]
+        ids = self.candidate_window(int(g))[:b]
+        return {"app": a, "group": int(g), "model": int(m), "batch": b, "score": float(cube[g, m, bi]),
                 "ids": ids.copy(), "t_start": self.t,
-                "t_end": self.start_time(int(a), int(m)) + self.lat[int(a)][int(m), bi]}
+                "t_end": self.start_time(a, int(m)) + self.lat[a][int(m), bi]}
 
     # -- commit ---------------------------------------------------------------
     def commit(self, a, m, ids):

@@ -75,6 +75,7 @@ class Policy:
     choice: int = CHOICE_UTILITY
     weight: int = WEIGHT_KEY
     batch_cap: int = 0                      # > 0: batches of at most this many requests
+    split_groups: int = 0                   # 1: data-aware subgroups per predicted class (Sec. 5.3.2)
 
 
 def named_policy(name: str) -> Policy:
