@@ -241,6 +241,14 @@ typedef enum { SP_CHOICE_UTILITY = 0, SP_CHOICE_MAX_ACCURACY = 1 } sp_choice;
 typedef enum { SP_WEIGHT_KEY = 0, SP_WEIGHT_UNIT = 1 } sp_weight;
 typedef struct {
   int32_t order, select, batch_rule, choice, weight, batch_cap;
+  int32_t split_groups;   /* 1: data-aware subgroups (Sec. 5.3.2, "Enhancements for Grouped Scheduling"): inside an
+                             application, requests whose SneakPeek head puts more than one half on a class form that
+                             class's subgroup, the others stay in the application's unsplit group; every non-empty
+                             (application, subgroup) pair is then a group of its own in the rounds (own service
+                             order, own candidate window; batches never mix subgroups; ties go to the smaller
+                             (application, subgroup)).  The label uses the head's own softmax output, also when a
+                             prior is set.  SP_ECAPACITY if sum_a (C_a + 1) exceeds 65536.  sp_schedule then runs
+                             two kernels per round, and SP_DUMP_SCORE_CUBE has one [Mmax, B] slab per group.       */
 } sp_policy;
 sp_status sp_set_policy(sp_ctx* ctx, const sp_policy* policy);
 

@@ -27,7 +27,7 @@ EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedul
 
 class sp_policy(C.Structure):
     _fields_ = [("order", C.c_int32), ("select", C.c_int32), ("batch_rule", C.c_int32), ("choice", C.c_int32),
-                ("weight", C.c_int32), ("batch_cap", C.c_int32)]
+                ("weight", C.c_int32), ("batch_cap", C.c_int32), ("split_groups", C.c_int32)]
 
 
 class sp_profile(C.Structure):
@@ -271,7 +271,7 @@ class Context:
         if policy is None:
             return self._check(self.lib.sp_set_policy(self.h, None), "sp_set_policy")
         st = sp_policy(int(policy.order), int(policy.select), int(policy.batch_rule), int(policy.choice),
-                       int(policy.weight), int(policy.batch_cap))
+                       int(policy.weight), int(policy.batch_cap), int(getattr(policy, "split_groups", 0)))
         return self._check(self.lib.sp_set_policy(self.h, C.byref(st)), "sp_set_policy")
 
     def sp_set_swap_cost(self, app, swap_ms):

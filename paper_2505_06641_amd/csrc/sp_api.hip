@@ -63,6 +63,12 @@ struct sp_ctx {
   float* d_ea_gain = nullptr;
   float* d_ea_bias = nullptr;
   float* d_swap = nullptr;
+  // data-aware group splitting (Sec. 5.3.2): one slot per possible (application, subgroup code)
+  int32_t n_slots = 0;
+  int32_t *slot_app = nullptr, *slot_base = nullptr, *slot_beg = nullptr, *slot_end = nullptr;
+  int32_t* h_grp_n = nullptr;        // pinned: number of groups of the scored window
+  hipEvent_t ev_groups = nullptr;    // recorded after the copy into h_grp_n
+  int sub_passes = 0;                // 8-bit radix passes over the subgroup codes
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -203,6 +209,7 @@ sp_status upload_heads(sp_ctx* c, const sp_profile* p) {
 sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p);
 sp_status pack_mlp_blocks(sp_ctx* c, const sp_profile* p);
 sp_status setup_persist(sp_ctx* c, const sp_profile* p);
+sp_status ensure_split_buffers(sp_ctx* c);
 int score_tile(const sp_ctx* c);
 
 sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
@@ -283,6 +290,11 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &w.key_s, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.alive_s, N + 16)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.head, 2 * (size_t)A)) != SP_OK) return s;
+  w.gcap = A;
+  w.sub_g = nullptr;
+  if ((s = dev_alloc(c, &w.grp_app, A)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.grp_end, A)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.grp_n, 1)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.model, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.round_of, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.order_of, N)) != SP_OK) return s;
@@ -445,6 +457,50 @@ sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
   return SP_OK;
 }
 
+// Buffers of the group-splitting mode (Sec. 5.3.2), allocated the first time it is switched on: the subgroup
+// code of every request, one slot per possible (application, code) pair, and per-group arrays large enough
+// for every non-empty pair.
+sp_status ensure_split_buffers(sp_ctx* c) {
+  if (c->w.sub_g) return SP_OK;
+  const int A = c->A;
+  int64_t slots = 0;
+  std::vector<int32_t> base(A), app_of;
+  int cmax = 0;
+  for (int a = 0; a < A; ++a) {
+    base[a] = (int32_t)slots;
+    slots += c->h_ncls[a] + 1;
+    cmax = std::max(cmax, c->h_ncls[a]);
+    if (slots > 65536) return SP_ECAPACITY;
+  }
+  app_of.reserve((size_t)slots);
+  for (int a = 0; a < A; ++a) app_of.insert(app_of.end(), (size_t)c->h_ncls[a] + 1, a);
+  c->n_slots = (int32_t)slots;
+  c->sub_passes = 1;
+  while ((1 << (8 * c->sub_passes)) <= cmax + 1) ++c->sub_passes;
+  const size_t gcap = (size_t)std::max<int64_t>(A, std::min<int64_t>(slots, std::max<int64_t>(c->cap, 1)));
+  Window& w = c->w;
+  sp_status s;
+  if ((s = dev_alloc(c, &w.sub_g, (size_t)std::max<int64_t>(c->cap, 1))) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->slot_app, app_of)) != SP_OK) return s;
+  if ((s = dev_upload(c, &c->slot_base, base)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->slot_beg, (size_t)slots)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->slot_end, (size_t)slots)) != SP_OK) return s;
+  // per-group arrays at the larger capacity (the old ones stay allocated until the context goes)
+  SP_HIP(c, hipDeviceSynchronize());
+  if ((s = dev_alloc(c, &w.grp_app, gcap)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.grp_end, gcap)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.head, 2 * gcap)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.cand, gcap * c->Mmax)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.cand_prio, gcap * c->Mmax)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.win_pos, gcap * c->B)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.win_n, gcap)) != SP_OK) return s;
+  w.gcap = (int32_t)gcap;
+  SP_HIP(c, hipHostMalloc((void**)&c->h_grp_n, sizeof(int32_t), hipHostMallocDefault));
+  *c->h_grp_n = A;
+  SP_HIP(c, hipEventCreate(&c->ev_groups));
+  return SP_OK;
+}
+
 sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p) {
   switch (c->mfma_D) {
     case 64: return pack_mfma_blocks_d<64>(c, p);
@@ -471,16 +527,15 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
                   uint32_t* sortkey, float* logits) {
   if (c->mlp_bf16) {
     const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
-    if (logits)
-      hipLaunchKernelGGL((k_score_mlp_bf16<true>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w, (const uint16_t*)x,
-                         ids, D, wt, sortkey, (const unsigned char*)c->w1p, (const int64_t*)c->w1_off,
-                         (const unsigned char*)c->blocks, (const int64_t*)c->block_off, (const float*)c->w_unscale,
-                         logits);
-    else
-      hipLaunchKernelGGL((k_score_mlp_bf16<false>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w, (const uint16_t*)x,
-                         ids, D, wt, sortkey, (const unsigned char*)c->w1p, (const int64_t*)c->w1_off,
-                         (const unsigned char*)c->blocks, (const int64_t*)c->block_off, (const float*)c->w_unscale,
-                         logits);
+#define SP_LAUNCH_MLP(DUMP, SPLIT)                                                                                \
+    hipLaunchKernelGGL((k_score_mlp_bf16<DUMP, SPLIT>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w,          \
+                       (const uint16_t*)x, ids, D, wt, sortkey, (const unsigned char*)c->w1p,                    \
+                       (const int64_t*)c->w1_off, (const unsigned char*)c->blocks, (const int64_t*)c->block_off, \
+                       (const float*)c->w_unscale, logits)
+    if (logits) SP_LAUNCH_MLP(true, false);
+    else if (c->tb.pol_split) SP_LAUNCH_MLP(false, true);
+    else SP_LAUNCH_MLP(false, false);
+#undef SP_LAUNCH_MLP
     return;
   }
   if (c->mfma_D > 0) {
@@ -489,11 +544,15 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
 #define SP_LAUNCH_MF(DD)                                                                                          \
     do {                                                                                                          \
       if (logits)                                                                                                 \
-        hipLaunchKernelGGL((k_score_logistic_split<DD, true>), dim3(grid), blk, 0, s, c->tb, c->w,                \
+        hipLaunchKernelGGL((k_score_logistic_split<DD, true, false>), dim3(grid), blk, 0, s, c->tb, c->w,         \
+                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
+      else if (c->tb.pol_split)                                                                                   \
+        hipLaunchKernelGGL((k_score_logistic_split<DD, false, true>), dim3(grid), blk, 0, s, c->tb, c->w,         \
                            (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
                            (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
       else                                                                                                        \
-        hipLaunchKernelGGL((k_score_logistic_split<DD, false>), dim3(grid), blk, 0, s, c->tb, c->w,               \
+        hipLaunchKernelGGL((k_score_logistic_split<DD, false, false>), dim3(grid), blk, 0, s, c->tb, c->w,        \
                            (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
                            (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
     } while (0)
@@ -521,8 +580,15 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, c
                      (const uint32_t*)c->hist, (const uint32_t*)c->scan_tot, keys_out, vals_out);
 }
 
+// Number of groups of the scored window: the applications, or the non-empty (application, subgroup) pairs.
+int group_count(sp_ctx* c) {
+  if (!c->tb.pol_split) return c->A;
+  (void)hipEventSynchronize(c->ev_groups);
+  return std::max(1, (int)*c->h_grp_n);
+}
+
 void launch_round(sp_ctx* c, hipStream_t s, int32_t* ids_out, float* cube) {
-  hipLaunchKernelGGL(k_round_score, dim3(c->A * c->Mmax), dim3(kRoundThreads), 0, s, c->tb, c->w, cube);
+  hipLaunchKernelGGL(k_round_score, dim3(group_count(c) * c->Mmax), dim3(kRoundThreads), 0, s, c->tb, c->w, cube);
   if (cube == nullptr)
     hipLaunchKernelGGL(k_round_commit, dim3(1), dim3(kRoundThreads), 0, s, c->tb, c->w, ids_out);
 }
@@ -581,6 +647,8 @@ void sp_destroy(sp_ctx* c) {
   for (void* p : c->dev_allocs) (void)hipFree(p);
   if (c->h_state) (void)hipHostFree(c->h_state);
   if (c->h_ticks) (void)hipHostFree(c->h_ticks);
+  if (c->h_grp_n) (void)hipHostFree(c->h_grp_n);
+  if (c->ev_groups) (void)hipEventDestroy(c->ev_groups);
   for (hipEvent_t e : c->ev)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->round_ev) (void)hipEventDestroy(e);
@@ -625,7 +693,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     }
   }
   hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, score_tile(c), unit, w.seg,
-                     w.tile_start, w.unit_start, w.head, w.tile_desc);
+                     w.tile_start, w.unit_start, w.tile_desc, w);
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;
@@ -645,8 +713,27 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       v_in = v_out;
       std::swap(v_out, v_spare);
     }
+    if (c->tb.pol_split) {
+      // subgroups: further stable passes over the subgroup codes make the order (subgroup, key) inside
+      // every application; then the non-empty (application, subgroup) pairs become the rounds' groups
+      hipLaunchKernelGGL(k_gather_sub_keys, dim3((n + 255) / 256), dim3(256), 0, s, A, (const int32_t*)w.seg, v_in,
+                         (const int32_t*)w.sub_g, k_in);
+      for (int p = 0; p < c->sub_passes; ++p) {
+        radix_pass(c, s, per_app, units2, k_in, v_in, 8 * p, k_out, v_out);
+        std::swap(k_in, k_out);
+        v_in = v_out;
+        std::swap(v_out, v_spare);
+      }
+    }
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
-                       (const uint32_t*)k_in, (const int32_t*)curV, w, c->tb.pol_edf);
+                       (const uint32_t*)k_in, (const int32_t*)curV, w, c->tb.pol_edf | c->tb.pol_split);
+    if (c->tb.pol_split) {
+      hipLaunchKernelGGL(k_slot_ranges, dim3((c->n_slots + 255) / 256), dim3(256), 0, s, c->n_slots,
+                         (const int32_t*)c->slot_app, (const int32_t*)c->slot_base, (const int32_t*)w.seg,
+                         (const uint32_t*)k_in, c->slot_beg, c->slot_end);
+      hipLaunchKernelGGL(k_groups_compact, dim3(1), dim3(1024), 0, s, c->n_slots, (const int32_t*)c->slot_app,
+                         (const int32_t*)c->slot_beg, (const int32_t*)c->slot_end, w);
+    }
     if (tm) {
       SP_HIP(c, hipEventRecord(c->ev[3], s));
       c->timed_score = true;
@@ -655,6 +742,11 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       SP_HIP(c, hipMemcpyAsync(ea_out_dev, w.ea, (size_t)n * c->Mmax * sizeof(float), hipMemcpyDeviceToDevice, s));
     if (key_out_dev)
       SP_HIP(c, hipMemcpyAsync(key_out_dev, w.key, (size_t)n * sizeof(float), hipMemcpyDeviceToDevice, s));
+  }
+  if (c->tb.pol_split) {
+    // the rounds' launch grids depend on the number of groups
+    SP_HIP(c, hipMemcpyAsync(c->h_grp_n, w.grp_n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    SP_HIP(c, hipEventRecord(c->ev_groups, s));
   }
   SP_HIP(c, hipGetLastError());
   c->scored = true;
@@ -693,10 +785,10 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   if (tm) SP_HIP(c, hipEventRecord(c->ev[4], s));
   c->round_ms.clear();
   while (!c->done) {
-    int chunk = c->persist ? kPersistRounds : 64;
+    const bool persist = c->persist && !c->tb.pol_split;     // the one-launch path iterates over applications
+    int chunk = persist ? kPersistRounds : 64;
     if (max_rounds > 0) chunk = std::min(chunk, start + max_rounds - c->rounds_done);
     if (chunk <= 0) break;
-    const bool persist = c->persist;
     const int32_t before = c->rounds_done;
     if (persist) {
       if ((st = launch_rounds_persistent(c, s, chunk)) != SP_OK) return st;
@@ -759,7 +851,7 @@ sp_status sp_debug_dump(sp_ctx* c, int32_t kind, void* stream, const void* x_dev
       SP_HIP(c, hipMemcpyAsync(dst_dev, c->w.seg, (size_t)(c->A + 1) * 4, hipMemcpyDeviceToDevice, s));
       break;
     case SP_DUMP_SCORE_CUBE: {
-      const int64_t cnt = (int64_t)c->A * c->Mmax * c->B;
+      const int64_t cnt = (int64_t)group_count(c) * c->Mmax * c->B;
       hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, (float*)dst_dev, cnt, -1.0f);
       launch_round(c, s, nullptr, (float*)dst_dev);
       break;
@@ -888,13 +980,21 @@ sp_status sp_set_policy(sp_ctx* c, const sp_policy* p) {
   sp_policy def{};
   if (!p) p = &def;
   if (p->order < 0 || p->order > 1 || p->select < 0 || p->select > 1 || p->batch_rule < 0 || p->batch_rule > 1 ||
-      p->choice < 0 || p->choice > 1 || p->weight < 0 || p->weight > 1 || p->batch_cap < 0)
+      p->choice < 0 || p->choice > 1 || p->weight < 0 || p->weight > 1 || p->batch_cap < 0 || p->split_groups < 0 ||
+      p->split_groups > 1)
     return SP_EINVAL;
   Tables& tb = c->tb;
   tb.pol_edf = p->order; tb.pol_group_first = p->select; tb.pol_whole = p->batch_rule;
   tb.pol_max_accuracy = p->choice; tb.pol_unit_weight = p->weight;
   tb.Bcap = p->batch_cap > 0 ? std::min(p->batch_cap, c->B) : c->B;
   c->scored = false;                 // the service order depends on the policy: score the window again
+  if (p->split_groups) {
+    DeviceGuard g(c->device);
+    if (!g.ok) return SP_EDEVICE;
+    sp_status s = ensure_split_buffers(c);
+    if (s != SP_OK) return s;
+  }
+  tb.pol_split = p->split_groups;
   return SP_OK;
 }
 
@@ -916,6 +1016,6 @@ sp_status sp_set_swap_cost(sp_ctx* c, int32_t app, const float* swap_ms_host) {
 
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
-int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist) ? 1 : 0; }
+int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist && !c->tb.pol_split) ? 1 : 0; }
 
 }  // extern "C"

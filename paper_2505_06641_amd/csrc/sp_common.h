@@ -24,6 +24,7 @@ struct Tables {
   int32_t pol_whole;          // 1: only the whole candidate window is a candidate batch
   int32_t pol_max_accuracy;   // 1: candidates are compared under the step penalty
   int32_t pol_unit_weight;    // 1: utilities of a batch are summed without the keys as weights
+  int32_t pol_split;          // 1: an application's requests are split into subgroups by predicted class (Sec. 5.3.2)
   int32_t Bcap;               // largest batch (<= B)
   float inv_timescale;
   const int32_t* n_classes;   // [A]
@@ -85,15 +86,22 @@ struct Window {
   float* w_s;                 // [n]
   float* key_s;               // [n]
   uint8_t* alive_s;           // [n] 1 = pending
-  int32_t* head;              // [2, A] first position that may still be live (double-buffered by round parity)
+  // Groups: what the rounds iterate over.  Without splitting, group g is application g; with it, the
+  // non-empty (application, subgroup) pairs in ascending order.  gcap = capacity of the per-group arrays.
+  int32_t gcap;
+  int32_t* sub_g;             // [n] subgroup code of the request at each grouped position: 0, or 1 + predicted class
+  int32_t* grp_app;           // [gcap] application of each group
+  int32_t* grp_end;           // [gcap] end of each group's range in service order
+  int32_t* grp_n;             // [1] number of groups
+  int32_t* head;              // [2, gcap] first position that may still be live (double-buffered by round parity)
   int32_t* model;             // [n] outputs, indexed by request id
   int32_t* round_of;          // [n]
   int32_t* order_of;          // [n]
   float* util;                // [n]
-  unsigned long long* cand;   // [A, Mmax] best packed candidate per (a, m) of the running round
-  float* cand_prio;           // [A, Mmax] group priority (eq. 14) of the application's window, per (a, m)
-  int32_t* win_pos;           // [A, B] service positions of each app's candidate window
-  int32_t* win_n;             // [A]
+  unsigned long long* cand;   // [gcap, Mmax] best packed candidate per (group, m) of the running round
+  float* cand_prio;           // [gcap, Mmax] group priority (eq. 14) of the group's window, per (group, m)
+  int32_t* win_pos;           // [gcap, B] service positions of each group's candidate window
+  int32_t* win_n;             // [gcap]
   Decision* log;              // [log_cap]
   int32_t log_cap;
   int32_t* last_ids;          // [B] members of the last committed batch

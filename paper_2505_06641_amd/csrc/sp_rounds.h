@@ -161,7 +161,9 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   __shared__ double dsum[kRoundThreads];
   const State* st = w.st;
   if (st->done || st->err) return;
-  const int a = blockIdx.x / tb.Mmax, m = blockIdx.x % tb.Mmax;
+  const int grp = blockIdx.x / tb.Mmax, m = blockIdx.x % tb.Mmax;   // group: an application, or one of its subgroups
+  if (grp >= *w.grp_n) return;
+  const int a = w.grp_app[grp];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int M = tb.n_models[a], B = tb.B, Bw = tb.Bcap;   // B: row stride of the tables; Bw: largest batch
   if (m >= M) {
@@ -172,8 +174,8 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   const double t = st->t;
   const int kind = tb.penalty[a];
   const double E0 = t + (double)tb.lmin[a];
-  const int seg_e = w.seg[a + 1];
-  const int head = w.head[(r & 1) * tb.A + a];
+  const int seg_e = w.grp_end[grp];
+  const int head = w.head[(r & 1) * w.gcap + grp];
 
   // ---- candidate window: first B live requests in service order ----
   // The first step looks at 4 positions per thread (1024 per workgroup, enough while most of the queue
@@ -227,10 +229,10 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   }
   const int nb = min(found, Bw);
   if (m == 0) {
-    for (int j = tid; j < nb; j += kRoundThreads) w.win_pos[a * B + j] = win[j];
+    for (int j = tid; j < nb; j += kRoundThreads) w.win_pos[grp * B + j] = win[j];
     if (tid == 0) {
-      w.win_n[a] = nb;
-      w.head[((r + 1) & 1) * tb.A + a] = nb > 0 ? win[0] : seg_e;
+      w.win_n[grp] = nb;
+      w.head[((r + 1) & 1) * w.gcap + grp] = nb > 0 ? win[0] : seg_e;
     }
   }
   if (nb == 0) {
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
   const double t0 = start_time(tb, st->last, t, a, m);
   unsigned long long best = triangle_best(scoring_penalty(tb, kind), ent, lat, nb, Bw, t0,
-                                          (uint32_t)((a * tb.Mmax + m) * B), cube_out, tb.pol_whole ? nb : 0);
+                                          (uint32_t)((grp * tb.Mmax + m) * B), cube_out, tb.pol_whole ? nb : 0);
   if (tb.pol_group_first) {
     // the group's priority (eq. 14) over the window; the same fixed-order sum in every kernel that forms it
     const double ps = block_sum_f64(tid < nb ? (double)ordering_value(tb, w, win[tid]) : 0.0, dsum);
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   if (st->done || st->err) return;
   const int tid = threadIdx.x;
   unsigned long long best = 0ull;
-  const int n_cand = tb.A * tb.Mmax;
+  const int n_cand = *w.grp_n * tb.Mmax;
   for (int i = tid; i < n_cand; i += kRoundThreads) {
     const unsigned long long c = w.cand[i];
     best = c > best ? c : best;
@@ -309,9 +311,9 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
         top = pk > top ? pk : top;
       }
     top = block_max_u64(top, red);
-    const int a_star = (int)(0xFFFFFFFFu - (uint32_t)(top & 0xFFFFFFFFull));
+    const int g_star = (int)(0xFFFFFFFFu - (uint32_t)(top & 0xFFFFFFFFull));
     best = 0ull;
-    for (int i = a_star * tb.Mmax + tid; i < (a_star + 1) * tb.Mmax; i += kRoundThreads) {
+    for (int i = g_star * tb.Mmax + tid; i < (g_star + 1) * tb.Mmax; i += kRoundThreads) {
       const unsigned long long c = w.cand[i];
       best = c > best ? c : best;
     }
@@ -322,13 +324,14 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   const int B = tb.B;
   const int b = (int)(cid % (uint32_t)B) + 1;
   const int am = (int)(cid / (uint32_t)B);
-  const int m = am % tb.Mmax, a = am / tb.Mmax;
+  const int m = am % tb.Mmax, grp = am / tb.Mmax;
+  const int a = w.grp_app[grp];
   const int r = st->round;
   const double t = st->t;
   const int next_order = st->next_order;
   const double E = start_time(tb, st->last, t, a, m) + (double)tb.lat[((int64_t)a * tb.Mmax + m) * B + (b - 1)];
   double wu, su, viol;
-  const int32_t* row = w.win_pos + a * B;
+  const int32_t* row = w.win_pos + grp * B;
   commit_members(tb, w, a, m, b, r, next_order, E, [&](int j) { return row[j]; }, ids_out, dsum, wu, su, viol);
   if (tid == 0) {
     Decision dc;

@@ -250,10 +250,10 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   const float lmin = tb.lmin[a];
   const float my_swap = tb.swap[a * tb.Mmax + m];
   int prev_a = st->last.app, prev_m = st->last.model;       // -1 before the window's first batch
-  const int seg_e = w.seg[a + 1];
+  const int seg_e = w.grp_end[a];                // this path runs unsplit: group a is application a
   int r = st->round;
   double t = st->t;
-  int scan_end = w.head[(r & 1) * tb.A + a];     // everything before it is consumed or dead
+  int scan_end = w.head[(r & 1) * w.gcap + a];   // everything before it is consumed or dead
   int nb = 0, shift = 0;
   for (int j = tid; j < B; j += kRoundThreads) lat_s[j] = tb.lat[((int64_t)a * tb.Mmax + m) * B + j];
   if (tid == 0) timed_out = 0;
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
     r += 1;
   }
   // first position of this application that may still be live, for whoever continues the window
-  if (m == 0 && tid == 0) w.head[(r & 1) * tb.A + a] = shift < nb ? win[shift] : scan_end;
+  if (m == 0 && tid == 0) w.head[(r & 1) * w.gcap + a] = shift < nb ? win[shift] : scan_end;
 }
 
 __global__ void k_fill_u64(unsigned long long* p, int64_t n, unsigned long long v) {

@@ -41,7 +41,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int MT>
 __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w, int a, int pos, int id, int M,
                                                const float (&ea_raw)[MT], const float* D, const float* wt,
-                                               uint32_t* sortkey) {
+                                               uint32_t* sortkey, int sub) {
+  if (tb.pol_split) w.sub_g[pos] = sub;
   // with a prior (Sec. 4.2 eq. (10)-(11)) the posterior is (alpha + k theta) / (sum alpha + k), and
   // eq. (9) on it is an affine map of eq. (9) on theta; gain 1 and bias 0 leave the value untouched
   float ea[MT];
@@ -140,8 +141,10 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
   // classes: lanes stride over c; online softmax state per (lane, request)
   constexpr float kNegBig = -1e30f;
   float mx[RW], sm[RW], ea[RW][MT];
+  int bestc[RW];                             // class of this lane's largest logit (subgroup label, Sec. 5.3.2)
 #pragma unroll
   for (int r = 0; r < RW; ++r) {
+    bestc[r] = 0x7fffffff;
     mx[r] = kNegBig;
     sm[r] = 0.f;
 #pragma unroll
@@ -167,6 +170,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
 #pragma unroll
       for (int r = 0; r < RW; ++r) {
         if (logits_out != nullptr && r < nr) logits_out[(int64_t)ids[p0 + r] * tb.Cmax + c] = z[r];
+        bestc[r] = z[r] > mx[r] ? c : bestc[r];
         const float mn = fmaxf(mx[r], z[r]);
         const float sc = expf(mx[r] - mn);
         const float p = expf(z[r] - mn);
@@ -187,7 +191,13 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
     float row[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) row[m] = wave_sum(ea[r][m] * f) / st;
-    if (lane == 0 && r < nr && logits_out == nullptr) finish_request<MT>(tb, w, a, p0 + r, ids[p0 + r], M, row, D, wt, sortkey);
+    // the largest posterior is exp(0) / st; its class is the smallest class among the lanes that hold the maximum
+    int cls = mx[r] == mt ? bestc[r] : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cls = min(cls, __shfl_xor(cls, o));
+    const int sub = (1.0f / st > 0.5f) ? 1 + cls : 0;
+    if (lane == 0 && r < nr && logits_out == nullptr)
+      finish_request<MT>(tb, w, a, p0 + r, ids[p0 + r], M, row, D, wt, sortkey, sub);
   }
 }
 

@@ -43,7 +43,7 @@ inline void pack_mlp_layer1(const uint16_t* W1 /*[d,H] bf16 bits*/, int d, int H
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const f32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <bool DUMP>
+template <bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     Tables tb, Window w, const uint16_t* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
     const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ w1p,
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     }
   }
 
-  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
                                   sortkey, logits_out);
 }
 

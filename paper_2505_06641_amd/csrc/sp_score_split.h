@@ -267,10 +267,10 @@ __device__ __forceinline__ float other_half(float v, int g) {
 
 // Softmax phase of one class tile (mostly vector ALU work): logits = acc * 2^-(ex+ew) + bias, online
 // softmax update, exponentials x table tile.
-template <int D, bool DUMP>
+template <int D, bool DUMP, bool SPLIT>
 __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, float unscale, f32x16& eacc, float& m2,
                                               int ct, int C, int g, int lane, bool valid, int64_t dump_row,
-                                              float* __restrict__ logits_out) {
+                                              float* __restrict__ logits_out, float& best_z, int& best_c) {
   using SB = SplitBlock<D>;
   // The other wavefront of this SIMD is, most of the time, streaming the MFMAs of its matrix phase and
   // always has the next one ready; without a higher priority the few MFMAs of this phase would wait
@@ -300,6 +300,16 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   float mt = acc[0];
 #pragma unroll
   for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[v]);
+  if (SPLIT && __builtin_amdgcn_ballot_w64(mt > best_z) != 0ull) {
+    // subgroup label (Sec. 5.3.2): class of the largest logit seen by this lane so far; equal logits keep
+    // the smallest class (v ascending is class ascending inside a lane)
+    int vi = 15;
+#pragma unroll
+    for (int v = 14; v >= 0; --v) vi = acc[v] == mt ? v : vi;
+    const bool up = mt > best_z;
+    best_c = up ? 32 * ct + 8 * (vi >> 2) + 4 * g + (vi & 3) : best_c;
+    best_z = up ? mt : best_z;
+  }
   mt = fmaxf(mt, other_half(mt, g));
   const float m2n = fmaxf(m2, mt * kLog2e);
   const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
@@ -335,7 +345,7 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
 // half-precision inputs (xh, xl; logits = unscale * W' x' + b), walk the application's packed blocks,
 // then EA, variance, key.  buf_a already holds (or is receiving by DMA) block 0; the caller has not yet
 // synchronised the workgroup on it.
-template <int D, bool DUMP>
+template <int D, bool DUMP, bool SPLIT>
 __device__ __forceinline__ void class_tiles_and_finish(
     const Tables& tb, const Window& w, float4* buf_a, float4* buf_b, float4* buf_c, const float4* __restrict__ src,
     const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale, int a, int CT, int C, int M, int pos, int id,
@@ -347,6 +357,8 @@ __device__ __forceinline__ void class_tiles_and_finish(
   __syncthreads();
 
   float m2 = kNegBig;                                    // running maximum, in units of log2
+  float best_z = kNegBig;                                // largest logit of this lane's classes and its class
+  int best_c = 0x7fffffff;
   f32x16 eacc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
@@ -383,9 +395,11 @@ __device__ __forceinline__ void class_tiles_and_finish(
       if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
       stage_park<D, 0>(FILL, stg, tid);   /* (past the last block: a copy nobody reads) */                     \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
-      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row,            \
+                                    logits_out, best_z, best_c);                                               \
     } else {                                                                                                   \
-      softmax_phase<D, DUMP>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row, logits_out);       \
+      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row,            \
+                                    logits_out, best_z, best_c);                                               \
       stage_park<D, 0>(FILL, stg, tid);                                                                        \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
       if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
@@ -433,6 +447,16 @@ __device__ __forceinline__ void class_tiles_and_finish(
     const int m = 8 * (v >> 2) + 4 * g + (v & 3);
     if (m < tb.Mmax) rowo[m] = ea[v];
   }
+  if (SPLIT) {
+    // the lane halves' candidates meet; the largest posterior is exp(z_max - reference) / sum
+    const float oz = other_half(best_z, g);
+    const int oc = __float_as_int(other_half(__int_as_float(best_c), g));
+    const bool take = oz > best_z || (oz == best_z && oc < best_c);
+    const float zmax = take ? oz : best_z;
+    const int cmax = take ? oc : best_c;
+    const float pmax = __builtin_amdgcn_exp2f(fmaf(zmax, kLog2e, kExpShift - m2));
+    if (g == 0) w.sub_g[pos] = (pmax * inv > 0.5f) ? 1 + cmax : 0;
+  }
   if (g == 0) {
     const float Di = Dl[id], wi = wt[id];
     uint32_t err = 0;
@@ -447,7 +471,7 @@ __device__ __forceinline__ void class_tiles_and_finish(
   }
 }
 
-template <int D, bool DUMP>
+template <int D, bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
     const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
@@ -545,7 +569,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       xl[q >> 3][q & 7] = lo[0]; xl[q >> 3][(q & 7) + 1] = lo[1];
     }
   }
-  class_tiles_and_finish<D, DUMP>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
                                   sortkey, logits_out);
 }
 

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
 // scoring tiles and sort units per application and the scoring tiles' descriptors.  One workgroup.
 __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
                                                   int tile, int unit, int32_t* seg, int32_t* tile_start,
-                                                  int32_t* unit_start, int32_t* head, int4* tile_desc) {
+                                                  int32_t* unit_start, int4* tile_desc, Window w) {
   for (int a = threadIdx.x; a <= A + 1; a += blockDim.x) {
     int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
     while (lo < hi) {
@@ -184,10 +184,14 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
     seg[a] = lo;                            // seg[A] = number of valid requests, seg[A+1] = n
   }
   __syncthreads();
+  // until (and unless) the requests are split into subgroups, group g is application g
   for (int a = threadIdx.x; a < A; a += blockDim.x) {
-    head[a] = seg[a];
-    head[A + a] = seg[a];
+    w.head[a] = seg[a];
+    w.head[w.gcap + a] = seg[a];
+    w.grp_app[a] = a;
+    w.grp_end[a] = seg[a + 1];
   }
+  if (threadIdx.x == 0) *w.grp_n = A;
   if (threadIdx.x == 0) {
     int ts = 0, us = 0;
     for (int a = 0; a < A; ++a) {
@@ -213,6 +217,75 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
       for (int t = 0; t < nt; ++t) tile_desc[t0 + t] = make_int4(a, sb + t * tile, se, 0);
     }
   }
+}
+
+// Subgroup codes as sort keys, in the current order of the passes' values (grouped positions).
+__global__ void k_gather_sub_keys(int n_valid_at, const int32_t* __restrict__ seg, const int32_t* __restrict__ grouped_pos,
+                                  const int32_t* __restrict__ sub_g, uint32_t* __restrict__ keys) {
+  const int pos = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pos < seg[n_valid_at]) keys[pos] = (uint32_t)sub_g[grouped_pos[pos]];
+}
+
+// Range of every possible (application, subgroup code) pair in the service order: two binary searches on
+// the sorted codes inside the application's range.  Slot s belongs to application slot_app[s] and code
+// s - slot_base[application].
+__global__ void k_slot_ranges(int n_slots, const int32_t* __restrict__ slot_app, const int32_t* __restrict__ slot_base,
+                              const int32_t* __restrict__ seg, const uint32_t* __restrict__ sub_sorted,
+                              int32_t* __restrict__ slot_beg, int32_t* __restrict__ slot_end) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= n_slots) return;
+  const int a = slot_app[s];
+  const uint32_t code = (uint32_t)(s - slot_base[a]);
+  const int b0 = seg[a], e0 = seg[a + 1];
+  int lo = b0, hi = e0;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (sub_sorted[mid] < code) lo = mid + 1; else hi = mid;
+  }
+  const int beg = lo;
+  hi = e0;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (sub_sorted[mid] <= code) lo = mid + 1; else hi = mid;
+  }
+  slot_beg[s] = beg;
+  slot_end[s] = lo;
+}
+
+// The non-empty slots, in slot order, become the groups of the rounds.  One workgroup.
+__global__ __launch_bounds__(1024) void k_groups_compact(int n_slots, const int32_t* __restrict__ slot_app,
+                                                         const int32_t* __restrict__ slot_beg,
+                                                         const int32_t* __restrict__ slot_end, Window w) {
+  __shared__ int wave_cnt[16];
+  __shared__ int base_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) base_s = 0;
+  __syncthreads();
+  for (int s0 = 0; s0 < n_slots; s0 += 1024) {
+    const int s = s0 + tid;
+    const bool full = s < n_slots && slot_end[s] > slot_beg[s];
+    const unsigned long long bal = __ballot(full);
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int before = base_s, total = 0;
+    for (int i = 0; i < 16; ++i) {
+      if (i < wave) before += wave_cnt[i];
+      total += wave_cnt[i];
+    }
+    if (full) {
+      const int j = before + __popcll(bal & ((1ull << lane) - 1ull));
+      if (j < w.gcap) {
+        w.grp_app[j] = slot_app[s];
+        w.grp_end[j] = slot_end[s];
+        w.head[j] = slot_beg[s];
+        w.head[w.gcap + j] = slot_beg[s];
+      }
+    }
+    __syncthreads();
+    if (tid == 0) base_s += total;
+    __syncthreads();
+  }
+  if (tid == 0) *w.grp_n = min(base_s, w.gcap);
 }
 
 // After the last pass.  The passes carried positions of the application-grouped array as values and the

@@ -69,9 +69,9 @@ def members_by_round(round_of, order_of, n_rounds):
     return [np.asarray(m, dtype=np.int64) for m in out]
 
 
-def replay(profile, requests, ea_ref, key_ref, log, members, done, tol, policy=None):
+def replay(profile, requests, ea_ref, key_ref, log, members, done, tol, policy=None, sub=None):
     """Replay the library's rounds in the oracle.  Returns (window, stats)."""
-    win = orc.Window(profile, requests, ea=ea_ref, key=key_ref, policy=policy)
+    win = orc.Window(profile, requests, ea=ea_ref, key=key_ref, policy=policy, sub=sub)
     stats = {"rounds": len(log), "exact": 0, "ties": 0, "max_score_rel": 0.0}
     for r, rec in enumerate(log):
         a, m, b = int(rec["app"]), int(rec["model"]), int(rec["batch"])
@@ -82,20 +82,21 @@ def replay(profile, requests, ea_ref, key_ref, log, members, done, tol, policy=N
         assert d is not None, f"round {r}: library committed a batch but nothing is live in the oracle"
         assert abs(rec["t_start_ms"] - win.t) <= 1e-9 * max(1.0, abs(win.t)), f"round {r}: clock {rec['t_start_ms']} vs {win.t}"
         exact = (d["app"], d["model"], d["batch"]) == (a, m, b) and np.array_equal(d["ids"], ids)
+        grp = int(win.gid[ids[0]])           # the group the library's batch belongs to
         kind = win.scoring_penalty(a)
         t_end = win.start_time(a, m) + win.lat[a][m, b - 1]
         mine = float((win.wsum[ids] * orc.utility(win.ea[ids, m], kind, win.D[ids], t_end)).sum())
         if exact:
             stats["exact"] += 1
         else:
-            live = win.live_queue(a)
+            live = win.live_queue(grp)
             assert np.all(np.isin(ids, live)), f"round {r}: a chosen request is not live in the oracle"
             best_here = d["score"]
-            if win.group_first and d["app"] != a:
+            if win.group_first and d["group"] != grp:
                 # a different group went first: its priority must tie the oracle's choice within tolerance
-                pa, pb = win.group_priority(a), win.group_priority(d["app"])
-                assert pa is not None and pa >= pb - tol * abs(pb), f"round {r}: group {a} ({pa!r}) is not the top group ({pb!r})"
-                best_here = float(np.max(cube[a]))
+                pa, pb = win.group_priority(grp), win.group_priority(d["group"])
+                assert pa is not None and pa >= pb - tol * abs(pb), f"round {r}: group {grp} ({pa!r}) is not the top group ({pb!r})"
+                best_here = float(np.max(cube[grp]))
             assert mine >= best_here * (1.0 - tol) - 1e-300, \
                 f"round {r}: library chose ({a},{m},{b}) worth {mine!r}, oracle best {d['score']!r} at " \
                 f"({d['app']},{d['model']},{d['batch']})"

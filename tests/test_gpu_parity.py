@@ -5,6 +5,8 @@ accuracies, keys, scores and utilities for float32 features; for the bfloat16
 config 2e-3 on posteriors (absolute) and on EA.  Decisions must match exactly
 or be tolerance ties as defined in tests/parity.py.
 """
+import copy
+
 import numpy as np
 import pytest
 
@@ -27,7 +29,7 @@ def gpu():
     return torch, binding
 
 
-def run_window(gpu, w, max_rounds, ctx=None, want_cube=False, policy=None):
+def run_window(gpu, w, max_rounds, ctx=None, want_cube=False, policy=None, n_groups=None):
     """Score + schedule one workload through the C ABI; everything back on the host."""
     torch, binding = gpu
     p, rq = w.profile, w.requests
@@ -46,7 +48,7 @@ def run_window(gpu, w, max_rounds, ctx=None, want_cube=False, policy=None):
     ctx.sp_debug_dump(binding.SP_DUMP_SEGMENTS, seg)
     out["order"], out["seg"] = order.cpu().numpy()[:n], seg.cpu().numpy()
     if want_cube:
-        cube = torch.zeros((p.n_apps, ctx.m_max, p.max_batch), device="cuda:0")
+        cube = torch.zeros((n_groups or p.n_apps, ctx.m_max, p.max_batch), device="cuda:0")
         ctx.sp_debug_dump(binding.SP_DUMP_SCORE_CUBE, cube)
         out["cube"] = cube.cpu().numpy()
     model = torch.full((max(n, 1),), 99, dtype=torch.int32, device="cuda:0")
@@ -65,26 +67,54 @@ def run_window(gpu, w, max_rounds, ctx=None, want_cube=False, policy=None):
 def full_parity(gpu, w, max_rounds, tol=TOL, ea_tol=None, want_cube=False, policy=None):
     torch, binding = gpu
     p, rq = w.profile, w.requests
+    sub, n_groups = None, None
+    if policy is not None and getattr(policy, "split_groups", 0):
+        # subgroup labels (Sec. 5.3.2) from the head's own posterior.  Requests whose largest probability
+        # is within 1e-4 of one half, where float32 and float64 may legitimately disagree about the label,
+        # are taken out of the window before either side sees it.
+        plain = copy.copy(p)
+        plain.prior_alpha = None
+        _, _, thetas = orc.score_requests(plain, rq, return_theta=True)
+        top = np.array([float(np.max(t)) for t in thetas])
+        keep = np.abs(top - 0.5) > 1e-4
+        if not keep.all():
+            rq = wl.Requests(x=rq.x[keep], app=rq.app[keep], deadline_rel_ms=rq.deadline_rel_ms[keep],
+                             weight=rq.weight[keep], label=None if rq.label is None else rq.label[keep])
+            w = copy.copy(w)
+            w.requests = rq
+            thetas = [t for t, k in zip(thetas, keep) if k]
+        sub = orc.split_labels(thetas)
+        n_groups = len(set(zip(rq.app.tolist(), sub.tolist())))
     ea_ref, key_ref = orc.score_requests(p, rq)
-    got = run_window(gpu, w, max_rounds, want_cube=want_cube, policy=policy)
+    got = run_window(gpu, w, max_rounds, want_cube=want_cube, policy=policy, n_groups=n_groups)
     stats = {}
     stats["ea_rel"] = parity.assert_close("EA", got["ea"], ea_ref, ea_tol or tol)
     stats["key_rel"] = parity.assert_close("key", got["key"], key_ref, ea_tol or tol, floor=1e-30)
     edf = policy is not None and policy.order == wl.ORDER_EDF
-    stats["order_swaps"] = parity.check_order(got["order"], got["seg"], rq.app,
-                                              -orc.widen(rq.deadline_rel_ms) if edf else key_ref, p.n_apps, tol)
+    omega = -orc.widen(rq.deadline_rel_ms) if edf else key_ref
+    if sub is None:
+        stats["order_swaps"] = parity.check_order(got["order"], got["seg"], rq.app, omega, p.n_apps, tol)
+    else:
+        # inside an application: subgroups in ascending order, each by descending ordering value
+        w0 = orc.Window(p, rq, ea=ea_ref, key=key_ref, policy=policy, sub=sub)
+        for a in range(p.n_apps):
+            want = np.concatenate([w0.order[g] for g in range(w0.G) if w0.gapp[g] == a] or [np.zeros(0, dtype=np.int64)])
+            have = got["order"][got["seg"][a]:got["seg"][a + 1]]
+            assert np.array_equal(have, want), f"app {a}: order inside the subgroups differs"
+        stats["order_swaps"] = 0
     if want_cube:
-        ref_cube = orc.Window(p, rq, ea=ea_ref, key=key_ref, policy=policy).score_cube()
+        ref_cube = orc.Window(p, rq, ea=ea_ref, key=key_ref, policy=policy, sub=sub).score_cube()
         valid = np.isfinite(ref_cube)
         assert np.array_equal(got["cube"] >= 0, valid), "candidate sets differ"
         stats["cube_rel"] = parity.assert_close("score cube", got["cube"][valid], ref_cube[valid], tol, floor=1e-12)
     members = parity.members_by_round(got["round_of"], got["order_of"], len(got["log"]))
     win, rstats = parity.replay(p, rq, ea_ref, key_ref, got["log"], members, got["summary"]["done"] == 1, tol,
-                                policy=policy)
+                                policy=policy, sub=sub)
     stats.update(rstats)
     stats["util_rel"] = parity.check_outputs(win, got["model"], got["round_of"], got["order_of"], got["util"],
                                              got["summary"], tol)
     got["close"]()
+    got["workload"] = w
     print(w.name, stats)
     return got, stats
 
@@ -342,6 +372,42 @@ def test_policies_of_the_evaluation_on_both_round_paths(gpu, name):
     with pytest.raises(binding.SneakPeekError) as e:
         ctx.sp_set_policy(bad)
     assert e.value.status == binding.SP_EINVAL
+    ctx.close()
+
+
+@pytest.mark.parametrize("head", ["logistic", "mlp_f32", "mlp_bf16"])
+@pytest.mark.parametrize("name", ["sneakpeek", "alg1"])
+def test_data_aware_group_splitting(gpu, head, name):
+    """Sec. 5.3.2: subgroups per predicted class, labelled by every scoring kernel, ordered and scheduled as
+    groups of their own."""
+    torch, binding = gpu
+    kw = dict(classes=(2, 5, 33, 3), models=(3, 2, 6, 4), max_batch=11, deadline=(6.0, 150.0), fractions=(0.3, 0.2, 0.3, 0.2))
+    if head == "logistic":
+        w = wl.tiny(seed=98, n=2200, feat_dim=19, hidden_dim=0, **kw)
+    elif head == "mlp_f32":
+        w = wl.tiny(seed=99, n=1100, feat_dim=33, hidden_dim=17, **kw)
+    else:
+        w = wl.tiny(seed=100, n=1300, feat_dim=24, hidden_dim=10, feat_dtype=wl.BF16, **kw)
+    for a in range(4):                          # sharper heads: a good share of confident requests
+        if w.profile.feat_dtype == wl.BF16:
+            w.profile.W1[a] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(w.profile.W1[a]) * 2.0)
+        else:
+            w.profile.W1[a] = (w.profile.W1[a] * 3.0).astype(np.float32)
+    policy = wl.named_policy(name)
+    policy.split_groups = 1
+    got, stats = full_parity(gpu, w, max_rounds=0, ea_tol=2e-3 if head == "mlp_bf16" else None, want_cube=True,
+                             policy=policy)
+    assert got["summary"]["done"] == 1 and stats["rounds"] > 10
+    # round by round gives the same schedule (on the window full_parity actually ran)
+    w = got["workload"]
+    ctx = binding.Context(w.profile, w.requests.n, policy=policy)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_score(x, app, D, wt)
+    assert not ctx.lib.sp_rounds_in_one_launch(ctx.h)
+    for rec in got["log"]:
+        rc, dec = ctx.sp_greedy_round()
+        assert rc == binding.SP_OK and dec == rec
+    assert ctx.sp_greedy_round()[0] == binding.SP_DONE
     ctx.close()
 
 
