@@ -80,9 +80,14 @@ def cpu_baseline(w, n_sample, rounds, policy=None):
     sub = wl.Requests(x=rq.x[:n_sample], app=rq.app[:n_sample], deadline_rel_ms=rq.deadline_rel_ms[:n_sample],
                       weight=rq.weight[:n_sample])
     t0 = time.perf_counter()
-    ea, key = orc.score_requests(w.profile, sub)
+    labels = None
+    if policy is not None and getattr(policy, "split_groups", 0):
+        ea, key, thetas = orc.score_requests(w.profile, sub, return_theta=True)
+        labels = orc.split_labels(thetas)
+    else:
+        ea, key = orc.score_requests(w.profile, sub)
     t1 = time.perf_counter()
-    win = orc.Window(w.profile, sub, ea=ea, key=key, policy=policy)
+    win = orc.Window(w.profile, sub, ea=ea, key=key, policy=policy, sub=labels)
     win.run(max_rounds=rounds)
     t2 = time.perf_counter()
     p = w.profile
@@ -104,6 +109,7 @@ def main():
     ap.add_argument("--policy", default="sneakpeek",
                     choices=["sneakpeek", "alg1", "lo_priority", "lo_edf", "maxacc_edf"],
                     help="scheduling policy (Sec. 6.1 baselines, Alg. 1 as printed); default: the joint arg max")
+    ap.add_argument("--split-groups", action="store_true", help="data-aware subgroups per predicted class (Sec. 5.3.2)")
     ap.add_argument("--priors", action="store_true", help="Dirichlet priors of the three kinds of Sec. 6.3 on the applications")
     ap.add_argument("--swap-costs", action="store_true", help="swap-in cost of 0.5-8 ms per variant")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -130,7 +136,9 @@ def main():
         wl.attach_priors(p, seed=1000 + w.seed)
     if args.swap_costs:
         wl.attach_swap_costs(p, seed=2000 + w.seed)
-    policy = None if args.policy == "sneakpeek" else wl.named_policy(args.policy)
+    policy = None if (args.policy == "sneakpeek" and not args.split_groups) else wl.named_policy(args.policy)
+    if args.split_groups:
+        policy.split_groups = 1
     ctx = binding.Context(p, n, policy=policy)
     x, app, D, wt = binding.to_device(rq)
     model = torch.empty(n, dtype=torch.int32, device="cuda:0")
@@ -213,7 +221,7 @@ def main():
                                f"N={n}, d={int(p.feat_dim)}, H={int(p.hidden_dim)}, seed {w.seed}; "
                                f"one scoring pass + {'greedy rounds until exhausted' if rounds <= 0 else str(rounds) + ' greedy rounds'}",
                    "n_requests": n, "rounds_run": n_rounds, "policy": args.policy, "priors": bool(args.priors),
-                   "swap_costs": bool(args.swap_costs),
+                   "swap_costs": bool(args.swap_costs), "split_groups": bool(args.split_groups),
                    "rounds_path": "one launch" if ctx.rounds_in_one_launch else "two kernels per round"},
         "greedy_round_latency_us": {"mean": float(np.mean(per_round)) if per_round else None,
                                     "p50": float(np.percentile(per_round, 50)) if per_round else None,
