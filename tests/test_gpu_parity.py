@@ -448,6 +448,21 @@ def test_swap_in_costs_on_both_round_paths(gpu, kind):
     ctx.close()
 
 
+def test_profile_too_large_for_the_one_launch_rounds_takes_the_two_kernel_path(gpu):
+    """More (application, variant) pairs than resident workgroups fit: sp_schedule falls back to two kernels
+    per round and takes the same decisions the oracle does."""
+    torch, binding = gpu
+    A = 90
+    w = wl.tiny(seed=101, n=5000, classes=tuple(2 + (a % 5) for a in range(A)), models=tuple(9 + (a % 4) for a in range(A)),
+                max_batch=7, feat_dim=12, deadline=(5.0, 90.0))
+    assert int(np.sum(w.profile.n_models)) > 900
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=False)
+    assert stats["rounds"] > 20 and got["summary"]["done"] == 1
+    ctx = binding.Context(w.profile, 5000)
+    assert not ctx.rounds_in_one_launch
+    ctx.close()
+
+
 def test_context_reuse_with_a_smaller_second_window(gpu):
     torch, binding = gpu
     big = wl.make("cfg2", n_requests=3000)
