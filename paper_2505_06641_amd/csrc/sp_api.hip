@@ -669,7 +669,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   c->rounds_done = 0;
   c->done = false;
   const int A = c->A;
-  hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(64), 0, s, w.st);
+  hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(64), 0, s, w.st, n, unit_size_for(n), c->seg1, c->unit1);
   const bool tm = c->timing && n > 0;
   c->timed_score = false;
   c->timed_rounds = false;
@@ -681,7 +681,6 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   if (n > 0) {
     // requests grouped by application: stable pass(es) over the application id
     hipLaunchKernelGGL(k_app_keys, dim3((n + 255) / 256), dim3(256), 0, s, n, app_dev, A, curK, w.st);
-    hipLaunchKernelGGL(k_single_segment, dim3(1), dim3(64), 0, s, n, unit, c->seg1, c->unit1);
     SortPlan whole{c->seg1, c->unit1, 1, unit};
     const int units1 = (n + unit - 1) / unit;
     const int32_t* vin = nullptr;
@@ -692,8 +691,10 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       vin = curV;
     }
   }
-  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, score_tile(c), unit, w.seg,
-                     w.tile_start, w.unit_start, w.tile_desc, w);
+  // a single pass over the application ids leaves every application's start in the scan's digit bases
+  const uint32_t* digit_base = (n > 0 && app_passes(A) == 1) ? (const uint32_t*)c->scan_tot : nullptr;
+  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, digit_base, score_tile(c), unit,
+                     w.seg, w.tile_start, w.unit_start, w.tile_desc, w);
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;
@@ -778,7 +779,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   hipStream_t s = (hipStream_t)stream;
   const int32_t start = c->rounds_done;
   sp_status st = SP_OK;
-  bool fetched = false;
+  bool fetched = false, outputs_copied = false;
   const bool tm = c->timing;
   c->n_round_ev = 0;
   c->timed_rounds = false;
@@ -801,6 +802,13 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
       }
     }
     if (tm) SP_HIP(c, hipEventRecord(c->ev[5], s));
+    // the per-request outputs go out right behind the rounds, so that the one host synchronisation of
+    // fetch_state covers them too (a later chunk simply copies again)
+    if (c->n > 0 && (model_out_dev || round_out_dev || order_out_dev || util_out_dev)) {
+      hipLaunchKernelGGL(k_copy_outputs, dim3((c->n + 255) / 256), dim3(256), 0, s, c->n, c->w, model_out_dev,
+                         round_out_dev, order_out_dev, util_out_dev);
+      outputs_copied = true;
+    }
     st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
     fetched = true;
     if (st != SP_OK) return st;
@@ -810,17 +818,18 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   }
   if (!fetched && (st = fetch_state(c, s)) != SP_OK) return st;
   c->timed_rounds = tm && fetched;
-  const size_t n = (size_t)c->n;
-  if (n > 0) {
-    if (model_out_dev) SP_HIP(c, hipMemcpyAsync(model_out_dev, c->w.model, n * 4, hipMemcpyDeviceToDevice, s));
-    if (round_out_dev) SP_HIP(c, hipMemcpyAsync(round_out_dev, c->w.round_of, n * 4, hipMemcpyDeviceToDevice, s));
-    if (order_out_dev) SP_HIP(c, hipMemcpyAsync(order_out_dev, c->w.order_of, n * 4, hipMemcpyDeviceToDevice, s));
-    if (util_out_dev) SP_HIP(c, hipMemcpyAsync(util_out_dev, c->w.util, n * 4, hipMemcpyDeviceToDevice, s));
+  bool pending = false;
+  if (c->n > 0 && !outputs_copied && (model_out_dev || round_out_dev || order_out_dev || util_out_dev)) {
+    hipLaunchKernelGGL(k_copy_outputs, dim3((c->n + 255) / 256), dim3(256), 0, s, c->n, c->w, model_out_dev,
+                       round_out_dev, order_out_dev, util_out_dev);
+    pending = true;
   }
   const int32_t n_log = std::min(std::min(c->rounds_done, log_capacity), c->w.log_cap);
-  if (n_log > 0)
+  if (n_log > 0) {
     SP_HIP(c, hipMemcpyAsync(round_log_host, c->w.log, (size_t)n_log * sizeof(sp_decision), hipMemcpyDeviceToHost, s));
-  SP_HIP(c, hipStreamSynchronize(s));
+    pending = true;
+  }
+  if (pending) SP_HIP(c, hipStreamSynchronize(s));
   if (out_host) {
     const State& h = *c->h_state;
     out_host->total_weighted_utility = h.total_wu;

@@ -350,9 +350,13 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   }
 }
 
-// Window state at the start of a window.
-__global__ void k_reset_state(State* st) {
+// Window state at the start of a window, and the one-segment plan of the pass over the application ids.
+__global__ void k_reset_state(State* st, int n, int unit, int32_t* seg1, int32_t* unit1) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
+    seg1[0] = 0;
+    seg1[1] = n;
+    unit1[0] = 0;
+    unit1[1] = (n + unit - 1) / unit;
     st->t = 0.0; st->total_wu = 0.0; st->total_u = 0.0; st->total_viol = 0.0;
     st->round = 0; st->next_order = 1; st->n_sched = 0; st->done = 0; st->err = 0u; st->pad = 0;
     st->last.app = -1; st->last.model = -1;      // nothing resident yet

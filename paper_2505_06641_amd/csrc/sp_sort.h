@@ -63,16 +63,6 @@ __global__ void k_app_keys(int n, const int32_t* __restrict__ app, int A, uint32
   if (!ok) atomicOr(&st->err, kErrApp);
 }
 
-// The whole queue as one segment.
-__global__ void k_single_segment(int n, int unit, int32_t* seg, int32_t* unit_start) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    seg[0] = 0;
-    seg[1] = n;
-    unit_start[0] = 0;
-    unit_start[1] = (n + unit - 1) / unit;
-  }
-}
-
 __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, const uint32_t* __restrict__ keys,
                                                                   int shift, uint32_t* __restrict__ hist) {
   __shared__ uint32_t cnt[kSortWaves][256];
@@ -95,6 +85,7 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, c
 // every 16th unit) and stores the column totals.  k_radix_scan_base: one workgroup per segment scans the
 // 256 totals and adds the segment start.  Offset of (unit u, digit d) = base[s][d] + hist[u][d].
 constexpr int kScanColThreads = 16;
+constexpr int kScanUnroll = 16;
 
 __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* __restrict__ hist,
                                                          uint32_t* __restrict__ tot /*[nseg,256]*/) {
@@ -103,17 +94,27 @@ __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* 
   const int dgt = dg * 16 + col;
   const int u0 = sp.unit_start[s], u1 = sp.unit_start[s + 1];
   uint32_t carry = 0;                                    // total of the column over the chunks done so far
-  for (int ub = u0; ub < u1; ub += kScanColThreads) {
-    const int u = ub + j;
-    const uint32_t c = u < u1 ? hist[(int64_t)u * 256 + dgt] : 0u;
-    uint32_t incl = c;
+  // kScanUnroll chunks per trip: their loads are independent of the carry and go out together, so a
+  // long column costs one memory round trip per kScanUnroll * 16 units instead of one per 16
+  for (int ub = u0; ub < u1; ub += kScanColThreads * kScanUnroll) {
+    uint32_t c[kScanUnroll];
 #pragma unroll
-    for (int o = 1; o < kScanColThreads; o <<= 1) {
-      const uint32_t up = __shfl_up(incl, o, kScanColThreads);
-      if (j >= o) incl += up;
+    for (int q = 0; q < kScanUnroll; ++q) {
+      const int u = ub + q * kScanColThreads + j;
+      c[q] = u < u1 ? hist[(int64_t)u * 256 + dgt] : 0u;
     }
-    if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c;
-    carry += __shfl(incl, kScanColThreads - 1, kScanColThreads);
+#pragma unroll
+    for (int q = 0; q < kScanUnroll; ++q) {
+      const int u = ub + q * kScanColThreads + j;
+      uint32_t incl = c[q];
+#pragma unroll
+      for (int o = 1; o < kScanColThreads; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o, kScanColThreads);
+        if (j >= o) incl += up;
+      }
+      if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c[q];
+      carry += __shfl(incl, kScanColThreads - 1, kScanColThreads);
+    }
   }
   if (j == 0) tot[(int64_t)s * 256 + dgt] = carry;
 }
@@ -172,10 +173,17 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
 // Segment starts from the application-sorted keys (values in [0, A], A =
 // invalid): seg[a] = first position with key >= a; then the prefixes of
 // scoring tiles and sort units per application and the scoring tiles' descriptors.  One workgroup.
+// digit_base, when given, holds the start of every digit of a single radix pass over the application ids:
+// the segment starts without any search.
 __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
-                                                  int tile, int unit, int32_t* seg, int32_t* tile_start,
-                                                  int32_t* unit_start, int4* tile_desc, Window w) {
+                                                  const uint32_t* __restrict__ digit_base, int tile, int unit,
+                                                  int32_t* seg, int32_t* tile_start, int32_t* unit_start,
+                                                  int4* tile_desc, Window w) {
   for (int a = threadIdx.x; a <= A + 1; a += blockDim.x) {
+    if (digit_base != nullptr) {
+      seg[a] = a <= A ? (int)digit_base[a] : n;
+      continue;
+    }
     int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
@@ -286,6 +294,17 @@ __global__ __launch_bounds__(1024) void k_groups_compact(int n_slots, const int3
     __syncthreads();
   }
   if (tid == 0) *w.grp_n = min(base_s, w.gcap);
+}
+
+// The four per-request outputs into the caller's arrays (any of them may be null), one launch.
+__global__ void k_copy_outputs(int n, Window w, int32_t* __restrict__ model, int32_t* __restrict__ round_of,
+                               int32_t* __restrict__ order_of, float* __restrict__ util) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  if (model) model[i] = w.model[i];
+  if (round_of) round_of[i] = w.round_of[i];
+  if (order_of) order_of[i] = w.order_of[i];
+  if (util) util[i] = w.util[i];
 }
 
 // After the last pass.  The passes carried positions of the application-grouped array as values and the
