@@ -140,10 +140,10 @@ inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/,
 // of a wavefront supplies the address of its own 16 bytes, the data lands at the (wave-uniform) LDS
 // base plus 16 * lane.  Used for the first block only: the instruction keeps the issuing wavefront
 // busy for about 300 cycles per KB on this part, too slow for the steady state.
-template <int D>
+template <int D, int WAVES = kMfWaves>
 __device__ __forceinline__ void stage_block_dma(const float4* __restrict__ src, float4* dst_lds, int wave, int lane) {
   using SB = SplitBlock<D>;
-  for (int ch = wave; ch < SB::kChunks; ch += kMfWaves)
+  for (int ch = wave; ch < SB::kChunks; ch += WAVES)
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + ch * 64 + lane),
                                      (void __attribute__((address_space(3)))*)(dst_lds + ch * 64), 16, 0, 0);
 }
@@ -341,6 +341,68 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   __builtin_amdgcn_s_setprio(0);
 }
 
+// After the last class tile: expected accuracies (eq. (9), with the prior's affine map), variance and key
+// (eq. (12)), the subgroup label, and the request's entries of the grouped arrays.
+template <bool SPLIT>
+__device__ __forceinline__ void score_epilogue(const Tables& tb, const Window& w, const f32x16& eacc, float m2,
+                                               float best_z, int best_c, int a, int M, int pos, int id, bool valid,
+                                               int r, int g, const float* __restrict__ Dl,
+                                               const float* __restrict__ wt, uint32_t* __restrict__ sortkey) {
+  // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
+  // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
+  const float ssum = __shfl(eacc[8], r);
+  const float inv = 1.0f / ssum;
+  // prior of Sec. 4.2 eq. (10)-(11) as an affine map of the expected accuracies (gain 1, bias 0 without one)
+  const float gain = tb.ea_gain[a];
+  const float* biasp = tb.ea_bias + a * tb.Mmax;
+  float ea[8];
+  float part = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    ea[v] = (m < M) ? fmaf(gain, eacc[v] * inv, biasp[m]) : 0.f;
+    part += ea[v];
+  }
+  const float mean = (part + __shfl_xor(part, 32)) / (float)M;
+  float vpart = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    const float dv = ea[v] - mean;
+    vpart += (m < M) ? dv * dv : 0.f;
+  }
+  const float var = (vpart + __shfl_xor(vpart, 32)) / (float)M;
+  if (!valid) return;
+  float* rowo = w.ea + (int64_t)id * tb.Mmax;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+    if (m < tb.Mmax) rowo[m] = ea[v];
+  }
+  if (SPLIT) {
+    // the lane halves' candidates meet; the largest posterior is exp(z_max - reference) / sum
+    const float oz = other_half(best_z, g);
+    const int oc = __float_as_int(other_half(__int_as_float(best_c), g));
+    const bool take = oz > best_z || (oz == best_z && oc < best_c);
+    const float zmax = take ? oz : best_z;
+    const int cmax = take ? oc : best_c;
+    const float pmax = __builtin_amdgcn_exp2f(fmaf(zmax, kLog2e, kExpShift - m2));
+    if (g == 0) w.sub_g[pos] = (pmax * inv > 0.5f) ? 1 + cmax : 0;
+  }
+  if (g == 0) {
+    const float Di = Dl[id], wi = wt[id];
+    uint32_t err = 0;
+    if (!(Di > 0.f)) err |= kErrDeadline;
+    if (!(wi >= 0.f)) err |= kErrWeight;
+    if (err) atomicOr(&w.st->err, err);
+    const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
+    w.key[id] = key;
+    sortkey[pos] = tb.pol_edf ? __float_as_uint(Di) : ~__float_as_uint(key);   // ascending deadline, or descending key
+    w.D_g[pos] = Di;
+    w.w_g[pos] = wi;
+  }
+}
+
 // Class tiles and epilogue shared by the scoring kernels: given the wavefront's 32 requests as split
 // half-precision inputs (xh, xl; logits = unscale * W' x' + b), walk the application's packed blocks,
 // then EA, variance, key.  buf_a already holds (or is receiving by DMA) block 0; the caller has not yet
@@ -415,93 +477,17 @@ __device__ __forceinline__ void class_tiles_and_finish(
   }
 #undef SP_TILE
   if (DUMP) return;
-
-  // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
-  // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
-  const float ssum = __shfl(eacc[8], r);
-  const float inv = 1.0f / ssum;
-  // prior of Sec. 4.2 eq. (10)-(11) as an affine map of the expected accuracies (gain 1, bias 0 without one)
-  const float gain = tb.ea_gain[a];
-  const float* biasp = tb.ea_bias + a * tb.Mmax;
-  float ea[8];
-  float part = 0.f;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    ea[v] = (m < M) ? fmaf(gain, eacc[v] * inv, biasp[m]) : 0.f;
-    part += ea[v];
-  }
-  const float mean = (part + __shfl_xor(part, 32)) / (float)M;
-  float vpart = 0.f;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    const float dv = ea[v] - mean;
-    vpart += (m < M) ? dv * dv : 0.f;
-  }
-  const float var = (vpart + __shfl_xor(vpart, 32)) / (float)M;
-  if (!valid) return;
-  float* rowo = w.ea + (int64_t)id * tb.Mmax;
-#pragma unroll
-  for (int v = 0; v < 8; ++v) {
-    const int m = 8 * (v >> 2) + 4 * g + (v & 3);
-    if (m < tb.Mmax) rowo[m] = ea[v];
-  }
-  if (SPLIT) {
-    // the lane halves' candidates meet; the largest posterior is exp(z_max - reference) / sum
-    const float oz = other_half(best_z, g);
-    const int oc = __float_as_int(other_half(__int_as_float(best_c), g));
-    const bool take = oz > best_z || (oz == best_z && oc < best_c);
-    const float zmax = take ? oz : best_z;
-    const int cmax = take ? oc : best_c;
-    const float pmax = __builtin_amdgcn_exp2f(fmaf(zmax, kLog2e, kExpShift - m2));
-    if (g == 0) w.sub_g[pos] = (pmax * inv > 0.5f) ? 1 + cmax : 0;
-  }
-  if (g == 0) {
-    const float Di = Dl[id], wi = wt[id];
-    uint32_t err = 0;
-    if (!(Di > 0.f)) err |= kErrDeadline;
-    if (!(wi >= 0.f)) err |= kErrWeight;
-    if (err) atomicOr(&w.st->err, err);
-    const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
-    w.key[id] = key;
-    sortkey[pos] = tb.pol_edf ? __float_as_uint(Di) : ~__float_as_uint(key);   // ascending deadline, or descending key
-    w.D_g[pos] = Di;
-    w.w_g[pos] = wi;
-  }
+  score_epilogue<SPLIT>(tb, w, eacc, m2, best_z, best_c, a, M, pos, id, valid, r, g, Dl, wt, sortkey);
 }
 
-template <int D, bool DUMP, bool SPLIT>
-__global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
-    Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
-    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
-    const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
-    float* __restrict__ logits_out) {
-  using SB = SplitBlock<D>;
-  // three separate arrays (not one array split in three) so that the compiler can tell that the
-  // blocks being read and the block being filled never overlap
-  __shared__ float4 buf_a[SB::kUnits];
-  __shared__ float4 buf_b[SB::kUnits];
-  __shared__ float4 buf_c[SB::kUnits];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// This lane's half of its request's features, k = g*D/2 + [0, D/2): the row scaled by a power of two into
+// (-2^15, 2^15) and split into half-precision hi and lo parts.  Returns the factor that undoes the scaling
+// of row and weights.  `scratch` is 8 x 66 units of LDS private to the wavefront.
+template <int D>
+__device__ __forceinline__ float load_split_features(const float* __restrict__ x, int id, int d, float4* scratch,
+                                                     int lane, float w_unscale_a, f16x8 (&xh)[D / 16],
+                                                     f16x8 (&xl)[D / 16]) {
   const int r = lane & 31, g = lane >> 5;
-  const int tile = blockIdx.x;
-  if (tile >= w.tile_start[tb.A]) return;
-  const int4 desc = w.tile_desc[tile];
-  const int a = desc.x, seg_e = desc.z;
-  const int pos = desc.y + wave * 32 + r;
-  const bool valid = pos < seg_e;
-  const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
-  const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];
-  const int CT = (C + kClassTile - 1) / kClassTile;
-
-  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
-  stage_block_dma<D>(src, buf_a, wave, lane);
-
-  // this lane's half of its request's features, k = g*D/2 + [0, D/2): scale the row into (-2^15, 2^15), split
-  f16x8 xh[D / 16], xl[D / 16];
-  float unscale;
-  {
     float xr[D / 2];
     const float* row = x + (int64_t)id * d;
     if (D == 256 && (d & 3) == 0) {
@@ -509,7 +495,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       // parks eight rows at a time in the block buffers that are still idle, and every lane then
       // picks its own half row out of LDS.  Row stride 66 and half offset 33 (in 16-byte units) keep
       // both the writes and the reads free of bank conflicts.
-      float4* scratch = (wave < kMfWaves / 2 ? buf_b : buf_c) + (wave % (kMfWaves / 2)) * (8 * 66);
+      // (scratch: this wavefront's own 8 x 66 units of an idle block buffer)
       // rows of pass ps+1 are already in flight while pass ps goes through LDS
       float4 rows[2][8];
       auto fetch_rows = [&](int ps, float4 (&dst)[8]) {
@@ -560,7 +546,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     int ex = 0;
     if (amax >= 1e-30f && amax <= 3e38f) ex = kSplitExp - (int)(((__float_as_uint(amax) >> 23) & 0xffu) - 126u);
     const float xs = __uint_as_float((uint32_t)(127 + ex) << 23);
-    unscale = __uint_as_float((uint32_t)(127 - ex) << 23) * w_unscale[a];
+    const float unscale = __uint_as_float((uint32_t)(127 - ex) << 23) * w_unscale_a;
 #pragma unroll
     for (int q = 0; q < D / 2; q += 2) {
       f16x2 hi, lo;
@@ -568,9 +554,42 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
       xh[q >> 3][q & 7] = hi[0]; xh[q >> 3][(q & 7) + 1] = hi[1];
       xl[q >> 3][q & 7] = lo[0]; xl[q >> 3][(q & 7) + 1] = lo[1];
     }
-  }
+  return unscale;
+}
+
+template <int D, bool DUMP, bool SPLIT>
+__global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
+    Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
+    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
+    const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
+    float* __restrict__ logits_out) {
+  using SB = SplitBlock<D>;
+  // three separate arrays (not one array split in three) so that the compiler can tell that the
+  // blocks being read and the block being filled never overlap
+  __shared__ float4 buf_a[SB::kUnits];
+  __shared__ float4 buf_b[SB::kUnits];
+  __shared__ float4 buf_c[SB::kUnits];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31;
+  const int tile = blockIdx.x;
+  if (tile >= w.tile_start[tb.A]) return;
+  const int4 desc = w.tile_desc[tile];
+  const int a = desc.x, seg_e = desc.z;
+  const int pos = desc.y + wave * 32 + r;
+  const bool valid = pos < seg_e;
+  const int id = ids[valid ? pos : seg_e - 1];           // padding lanes recompute the last request, never store
+  const int d = tb.d, C = tb.n_classes[a], M = tb.n_models[a];
+  const int CT = (C + kClassTile - 1) / kClassTile;
+
+  const float4* src = reinterpret_cast<const float4*>(blocks + block_off[a]);
+  stage_block_dma<D>(src, buf_a, wave, lane);
+
+  f16x8 xh[D / 16], xl[D / 16];
+  float4* scratch = (wave < kMfWaves / 2 ? buf_b : buf_c) + (wave % (kMfWaves / 2)) * (8 * 66);
+  const float unscale = load_split_features<D>(x, id, d, scratch, lane, w_unscale[a], xh, xl);
   class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
                                   sortkey, logits_out);
 }
+
 
 }  // namespace sp
