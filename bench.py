@@ -232,7 +232,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 65536, "cfg5": 524288}[args.workload]
+        default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 65536, "cfg5": 1048576}[args.workload]
         ns = min(n, args.cpu_sample or default_sample)
         out["cpu_baseline"] = cpu_baseline(w, ns, rounds, policy)
     ctx.close()
