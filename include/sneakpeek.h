@@ -37,7 +37,8 @@ typedef enum {
   SP_DONE = 1,        /* no live request is left: not an error                   */
   SP_EINVAL = -1,     /* bad argument, bad profile, or bad request data          */
   SP_ENOMEM = -2,     /* host or device allocation failed                        */
-  SP_EDEVICE = -3,    /* a HIP call failed (see sp_last_hip_error)               */
+  SP_EDEVICE = -3,    /* a HIP call failed, or resident workgroups of the rounds
+                         kernel lost each other (see sp_last_hip_error)          */
   SP_ESTATE = -4,     /* call order: rounds before any sp_score                  */
   SP_ECAPACITY = -5   /* a size exceeds what the context or library supports     */
 } sp_status;
@@ -173,7 +174,13 @@ sp_status sp_greedy_round(sp_ctx* ctx, void* stream, sp_decision* out_host, int3
  *     far (including earlier sp_greedy_round calls), truncated to capacity.
  *   out_host: totals over the window so far.
  * Returns SP_OK when stopped by max_rounds, SP_DONE when the queue is
- * exhausted (both fill the outputs).                                           */
+ * exhausted (both fill the outputs).
+ * When every (application, variant) pair fits on the device at once (see
+ * sp_rounds_in_one_launch), up to 64 rounds run inside one kernel whose
+ * workgroups wait for each other with bounded waits.  If the device is shared
+ * with other long-running work and such a wait runs out, the call returns
+ * SP_EDEVICE, the context switches to two kernels per round for good, and the
+ * window has to be scored again (SP_ESTATE until then).                        */
 sp_status sp_schedule(sp_ctx* ctx, int32_t max_rounds, void* stream,
                       int32_t* model_out_dev, int32_t* round_out_dev, int32_t* order_out_dev,
                       float* util_out_dev, sp_decision* round_log_host, int32_t log_capacity,
@@ -186,12 +193,13 @@ sp_status sp_debug_dump(sp_ctx* ctx, int32_t kind, void* stream, const void* x_d
                         const int32_t* app_dev, void* dst_dev);
 
 /* Benchmark aid.  sp_set_timing(ctx, 1) makes sp_score and sp_schedule record
- * HIP events around their stages; sp_set_timing(ctx, 2) additionally records
- * one after each of the first 4096 rounds (this slows the rounds down a little);
- * sp_get_timing / sp_get_round_times wait for those events and return the
- * elapsed device times (per-round times in milliseconds, HOST array of
- * `capacity` floats, *n_out = number written).  SP_ESTATE if timing is off or
- * nothing has been recorded yet.                                              */
+ * HIP events around their stages; sp_set_timing(ctx, 2) additionally times
+ * every round: from the rounds kernel's own constant-rate timestamps when the
+ * rounds run in one launch, else from one HIP event after each of the first
+ * 4096 rounds (this slows the rounds down a little).  sp_get_timing /
+ * sp_get_round_times wait for the events and return the elapsed device times
+ * (per-round times in milliseconds, HOST array of `capacity` floats, *n_out =
+ * number written).  SP_ESTATE if timing is off or nothing has been recorded yet. */
 sp_status sp_set_timing(sp_ctx* ctx, int32_t enable);
 sp_status sp_get_timing(sp_ctx* ctx, sp_timing* out_host);
 sp_status sp_get_round_times(sp_ctx* ctx, float* ms_out_host, int32_t capacity, int32_t* n_out);

@@ -1,19 +1,19 @@
-// One greedy batch-selection round (Alg. 1 generalised to batch-capped rounds;
-// eq. (2) utility; eq. (13) arg max; eq. (1) clock with the batch as the unit).
+// One greedy batch-selection round as two kernels (Alg. 1 generalised to batch-capped rounds; eq. (2)
+// utility; eq. (13) arg max; eq. (1) clock with the batch as the unit), and the device functions that the
+// one-launch rounds kernel shares with them (triangle_best, commit_members, start_time, ...).
 //
-// k_round_score: one workgroup per (application, variant).  It walks the
-// application's service order from the head pointer, keeps the first B live
-// requests (pending, and penalty on the earliest possible completion below 1)
-// as the candidate window, and evaluates
-//   Score[a,m,b] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
-// for every b, pairing batch sizes b and B+1-b on the same lanes so that all
-// lanes do the same amount of work.  Its best (score, candidate id) goes to
-// cand[a,m] as one 64-bit word whose unsigned order is (score ascending,
-// candidate id descending): the maximum is the best score and, among equal
-// scores, the smallest (a, m, b).
-// k_round_commit: one workgroup.  Takes the maximum over cand, assigns the
-// chosen requests, clears their pending flags, appends the decision to the
-// log and advances the clock.
+// A group is what a round iterates over: an application, or (Sec. 5.3.2) one of its subgroups.
+// k_round_score: one workgroup per (group, variant).  It walks the group's service order from the head
+// pointer, keeps the first B live requests (pending, and penalty on the earliest possible completion
+// below 1) as the candidate window, and evaluates
+//   Score[g,m,b] = sum_{j<=b} key_j * EA[j,m] * (1 - gamma_a(D_j, t + L[a][m][b]))
+// for every b, pairing batch sizes b and B+1-b on the same lanes so that all lanes do the same amount
+// of work.  Its best (score, candidate id) goes to cand[g,m] as one 64-bit word whose unsigned order is
+// (score ascending, candidate id descending): the maximum is the best score and, among equal scores,
+// the smallest (g, m, b).  The policy knobs of Sec. 6.1 change what is summed (weights, penalty used
+// for the comparison), which batch sizes are candidates, and how the maximum is taken (group first).
+// k_round_commit: one workgroup.  Takes the maximum over cand, assigns the chosen requests, clears their
+// pending flags, appends the decision to the log and advances the clock.
 #pragma once
 #include "sp_common.h"
 

@@ -3,12 +3,14 @@
 // window: once over the whole queue with the application id as the key (the
 // request groups of Alg. 1, "HashMap<app : request list>"), then four times
 // inside each application's range with the inverted bits of the priority key
-// (Alg. 1, "requests in g sorted by priority"; eq. (12)).
+// (Alg. 1, "requests in g sorted by priority"; eq. (12)) or the bits of the
+// deadline (earliest deadline first), and, with data-aware subgroups
+// (Sec. 5.3.2), once or twice more with the subgroup label.
 //
 // The unit of work is one wavefront walking `unit` consecutive elements of one
 // segment 64 at a time, in order; units never straddle segments.  A pass is
-// three kernels: per-unit digit histograms, one scan per segment in
-// (digit, unit) order, and the scatter, in which every wavefront ranks its 64
+// four kernels: per-unit digit histograms, a scan down every (segment, digit)
+// column, a scan over each segment's 256 column totals, and the scatter, in which every wavefront ranks its 64
 // elements per digit with ballots (equal digits keep their order) and bumps a
 // wavefront-private running offset table in LDS.  No inter-workgroup waiting.
 #pragma once
