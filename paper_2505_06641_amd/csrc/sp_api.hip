@@ -575,7 +575,6 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, c
   const int blocks = (max_units + kSortWaves - 1) / kSortWaves;
   hipLaunchKernelGGL(k_radix_hist, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, shift, c->hist);
   hipLaunchKernelGGL(k_radix_scan_cols, dim3(plan.nseg * 16), dim3(256), 0, s, plan, c->hist, c->scan_tot);
-  hipLaunchKernelGGL(k_radix_scan_base, dim3(plan.nseg), dim3(256), 0, s, plan, c->scan_tot);
   hipLaunchKernelGGL(k_radix_scatter, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, vals, shift,
                      (const uint32_t*)c->hist, (const uint32_t*)c->scan_tot, keys_out, vals_out);
 }
@@ -691,9 +690,9 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       vin = curV;
     }
   }
-  // a single pass over the application ids leaves every application's start in the scan's digit bases
-  const uint32_t* digit_base = (n > 0 && app_passes(A) == 1) ? (const uint32_t*)c->scan_tot : nullptr;
-  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, digit_base, score_tile(c), unit,
+  // a single pass over the application ids leaves every application's count in the scan's digit totals
+  const uint32_t* digit_tot = (n > 0 && app_passes(A) == 1) ? (const uint32_t*)c->scan_tot : nullptr;
+  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, digit_tot, score_tile(c), unit,
                      w.seg, w.tile_start, w.unit_start, w.tile_desc, w);
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features

@@ -84,8 +84,9 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, c
 // Destination offsets from the per-unit counts, in two small kernels.
 // k_radix_scan_cols: workgroup (segment s, digit group dg) turns the 16 columns hist[.][16 dg .. 16 dg + 15]
 // of the segment's units into exclusive prefixes down the column (16 threads per column, each walking
-// every 16th unit) and stores the column totals.  k_radix_scan_base: one workgroup per segment scans the
-// 256 totals and adds the segment start.  Offset of (unit u, digit d) = base[s][d] + hist[u][d].
+// every 16th unit) and stores the column totals.  The exclusive scan over a segment's 256 totals is cheap
+// enough for every scattering wavefront to redo it for itself (wave_digit_bases), which saves a launch per
+// pass.  Offset of (unit u, digit d) = seg[s] + (totals of s before d) + hist[u][d].
 constexpr int kScanColThreads = 16;
 constexpr int kScanUnroll = 16;
 
@@ -121,34 +122,42 @@ __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* 
   if (j == 0) tot[(int64_t)s * 256 + dgt] = carry;
 }
 
-__global__ __launch_bounds__(256) void k_radix_scan_base(SortPlan sp, uint32_t* __restrict__ tot) {
-  __shared__ uint32_t sc[256];
-  const int s = blockIdx.x, dgt = threadIdx.x;
-  const uint32_t mine = tot[(int64_t)s * 256 + dgt];
-  sc[dgt] = mine;
-  __syncthreads();
-  for (int o = 1; o < 256; o <<= 1) {                    // Hillis-Steele inclusive scan in LDS
-    const uint32_t v = (dgt >= o) ? sc[dgt - o] : 0u;
-    __syncthreads();
-    sc[dgt] += v;
-    __syncthreads();
+// Start of every digit of segment s, given the segment's 256 digit totals: lane l returns the starts of
+// digits 4l .. 4l+3.
+__device__ __forceinline__ uint4 wave_digit_bases(const uint32_t* __restrict__ tot_s, uint32_t seg_start, int lane) {
+  const uint4 t = *reinterpret_cast<const uint4*>(tot_s + 4 * lane);
+  const uint32_t mine = t.x + t.y + t.z + t.w;
+  uint32_t incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
   }
-  tot[(int64_t)s * 256 + dgt] = (uint32_t)sp.seg[s] + sc[dgt] - mine;
+  uint4 b;
+  b.x = seg_start + incl - mine;
+  b.y = b.x + t.x;
+  b.z = b.y + t.y;
+  b.w = b.z + t.z;
+  return b;
 }
 
 // vals_in == nullptr means the identity (value = element index).
 __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
     SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift,
-    const uint32_t* __restrict__ offs, const uint32_t* __restrict__ base, uint32_t* __restrict__ keys_out,
+    const uint32_t* __restrict__ offs, const uint32_t* __restrict__ tot, uint32_t* __restrict__ keys_out,
     int32_t* __restrict__ vals_out) {
-  __shared__ uint32_t run[kSortWaves][256];
+  __shared__ __align__(16) uint32_t run[kSortWaves][256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int u = blockIdx.x * kSortWaves + wave;
   int beg = 0, end = 0;
   const bool have = unit_range(sp, u, beg, end);
   if (!have) return;   // no block-wide barrier below: wavefronts are independent
   const int sg = find_segment(sp.unit_start, sp.nseg, u);
-  for (int i = lane; i < 256; i += 64) run[wave][i] = offs[(int64_t)u * 256 + i] + base[(int64_t)sg * 256 + i];
+  {
+    const uint4 b = wave_digit_bases(tot + (int64_t)sg * 256, (uint32_t)sp.seg[sg], lane);
+    const uint4 o = *reinterpret_cast<const uint4*>(offs + (int64_t)u * 256 + 4 * lane);
+    *reinterpret_cast<uint4*>(&run[wave][4 * lane]) = make_uint4(o.x + b.x, o.y + b.y, o.z + b.z, o.w + b.w);
+  }
   wave_sync();
   const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int base = beg; base < end; base += 64) {
@@ -175,17 +184,24 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
 // Segment starts from the application-sorted keys (values in [0, A], A =
 // invalid): seg[a] = first position with key >= a; then the prefixes of
 // scoring tiles and sort units per application and the scoring tiles' descriptors.  One workgroup.
-// digit_base, when given, holds the start of every digit of a single radix pass over the application ids:
-// the segment starts without any search.
+// digit_tot, when given, holds the count of every digit of a single radix pass over the application ids
+// (wavefront 0 turns them into the segment starts without any search).
 __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
-                                                  const uint32_t* __restrict__ digit_base, int tile, int unit,
+                                                  const uint32_t* __restrict__ digit_tot, int tile, int unit,
                                                   int32_t* seg, int32_t* tile_start, int32_t* unit_start,
                                                   int4* tile_desc, Window w) {
-  for (int a = threadIdx.x; a <= A + 1; a += blockDim.x) {
-    if (digit_base != nullptr) {
-      seg[a] = a <= A ? (int)digit_base[a] : n;
-      continue;
+  if (digit_tot != nullptr) {
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x;
+      const uint4 b = wave_digit_bases(digit_tot, 0u, lane);
+      const uint32_t bb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (4 * lane + q <= A) seg[4 * lane + q] = (int)bb[q];
+      if (lane == 0) seg[A + 1] = n;
     }
+  }
+  for (int a = threadIdx.x; a <= A + 1 && digit_tot == nullptr; a += blockDim.x) {
     int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
