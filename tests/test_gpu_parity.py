@@ -463,6 +463,37 @@ def test_profile_too_large_for_the_one_launch_rounds_takes_the_two_kernel_path(g
     ctx.close()
 
 
+def test_more_than_255_applications_two_pass_grouping(gpu):
+    """Two radix passes over the application id, segment starts by search, many empty and tiny groups."""
+    A = 300
+    rng = np.random.default_rng(7)
+    frac = rng.dirichlet(np.full(A, 0.3))
+    w = wl.tiny(seed=102, n=4000, classes=tuple(2 + (a % 3) for a in range(A)), models=tuple(1 + (a % 3) for a in range(A)),
+                max_batch=6, feat_dim=10, deadline=(5.0, 90.0), fractions=tuple(frac / frac.sum()))
+    counts = np.bincount(w.requests.app, minlength=A)
+    assert (counts == 0).any() and counts.max() > 50
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True)
+    assert got["summary"]["done"] == 1 and stats["rounds"] >= 20
+
+
+def test_largest_batch_variant_and_class_counts(gpu):
+    """B = 256 and M = 16 (the library's limits) with C well beyond one class tile, on the matrix-core kernel."""
+    w = wl.tiny(seed=103, n=900, classes=(1500, 700), models=(16, 16), max_batch=256, feat_dim=64, deadline=(20.0, 900.0),
+                alpha=(0.5, 3.0), beta=(0.05, 0.4))
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True)
+    assert max(r["batch"] for r in got["log"]) > 64 and got["summary"]["done"] == 1
+
+
+def test_bf16_logistic_head_and_wide_fp32_head(gpu):
+    """Heads outside the matrix-core kernels' shapes run on the generic kernel: bf16 without a hidden layer,
+    fp32 wider than 256 features."""
+    w = wl.tiny(seed=104, n=500, classes=(6, 11), models=(3, 4), max_batch=7, feat_dim=40, hidden_dim=0,
+                feat_dtype=wl.BF16, deadline=(5.0, 90.0))
+    full_parity(gpu, w, max_rounds=0, ea_tol=2e-3)
+    w = wl.tiny(seed=105, n=300, classes=(9, 4), models=(2, 5), max_batch=5, feat_dim=300, hidden_dim=0, deadline=(5.0, 90.0))
+    full_parity(gpu, w, max_rounds=0, want_cube=True)
+
+
 def test_context_reuse_with_a_smaller_second_window(gpu):
     torch, binding = gpu
     big = wl.make("cfg2", n_requests=3000)
