@@ -176,6 +176,17 @@ def main():
     ctx.sp_set_timing(2)
     step()
     per_round = [v * 1e3 for v in ctx.sp_get_round_times()][:max(1, n_rounds)]
+    # and the latency of single sp_greedy_round calls (one round per call, host synchronisation included)
+    ctx.sp_set_timing(0)
+    ctx.sp_score(x, app, D, wt)
+    torch.cuda.synchronize()
+    call_us = []
+    for _ in range(max(1, min(n_rounds, 64))):
+        c0 = time.perf_counter()
+        rc, _ = ctx.sp_greedy_round()
+        call_us.append((time.perf_counter() - c0) * 1e6)
+        if rc != binding.SP_OK:
+            break
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     cand = float(n) * m_max * B
     value = cand / (ms_per_step * 1e-3)
@@ -226,7 +237,9 @@ def main():
         "greedy_round_latency_us": {"mean": float(np.mean(per_round)) if per_round else None,
                                     "p50": float(np.percentile(per_round, 50)) if per_round else None,
                                     "p99": float(np.percentile(per_round, 99)) if per_round else None,
-                                    "rounds": len(per_round)},
+                                    "rounds": len(per_round),
+                                    "single_call_mean": float(np.mean(call_us)), "single_call_p50": float(np.percentile(call_us, 50)),
+                                    "single_call_p99": float(np.percentile(call_us, 99))},
         "stage_ms": {"group_by_app": float(np.mean(group_ms)), "score_kernel": k_avg,
                      "order_by_key": float(np.mean(order_ms)), "rounds": float(np.mean(rounds_ms))},
         "roofline": roof,
