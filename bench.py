@@ -117,7 +117,7 @@ def main():
                          "the known-size kernel that hardware byte counters of a profiler run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by application, see DESIGN.md); "
+        print("bench.py: this build runs on one GPU only (the path would shard by application); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
