@@ -207,6 +207,20 @@ def test_dirichlet_priors_on_every_scoring_kernel(gpu, head):
     full_parity(gpu, w, max_rounds=0, ea_tol=2e-3 if head == "mlp_bf16" else None, want_cube=head != "mlp_bf16")
 
 
+@pytest.mark.parametrize("name", ["sneakpeek", "alg1"])
+def test_data_oblivious_baselines_are_a_prior_without_evidence(gpu, name):
+    """Sec. 6.1: the data-oblivious approaches use the profiled accuracy under the profiling label mix for
+    every request of an application: a prior equal to that mix and no evidence (Sec. 4.1, fallback of eq. 9)."""
+    w = wl.tiny(seed=96, n=1800, classes=(5, 12, 40), models=(3, 2, 6), max_batch=7, feat_dim=21, deadline=(4.0, 90.0))
+    wl.attach_priors(w.profile, seed=97, kinds=("weak", "strong"))
+    w.profile.evidence_k[:] = 0.0
+    ea_ref, _ = orc.score_requests(w.profile, w.requests)
+    for a in range(3):
+        rows = ea_ref[w.requests.app == a]
+        assert np.ptp(rows, axis=0).max() == 0.0          # one row per application, whatever the request holds
+    full_parity(gpu, w, max_rounds=0, policy=wl.named_policy(name), want_cube=True)
+
+
 def test_prior_can_be_removed_and_bad_priors_are_rejected(gpu):
     torch, binding = gpu
     w = wl.tiny(seed=94, n=300, classes=(4, 6), models=(2, 3), max_batch=4, feat_dim=8)
