@@ -574,7 +574,11 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, c
                 const int32_t* vals, int shift, uint32_t* keys_out, int32_t* vals_out) {
   const int blocks = (max_units + kSortWaves - 1) / kSortWaves;
   hipLaunchKernelGGL(k_radix_hist, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, shift, c->hist);
-  hipLaunchKernelGGL(k_radix_scan_cols, dim3(plan.nseg * 16), dim3(256), 0, s, plan, c->hist, c->scan_tot);
+  // a wavefront per digit column once the segments average more than one trip of the narrow scan
+  if (max_units / plan.nseg > 16 * kScanUnroll)
+    hipLaunchKernelGGL(k_radix_scan_cols<64>, dim3(plan.nseg * 64), dim3(256), 0, s, plan, c->hist, c->scan_tot);
+  else
+    hipLaunchKernelGGL(k_radix_scan_cols<16>, dim3(plan.nseg * 16), dim3(256), 0, s, plan, c->hist, c->scan_tot);
   hipLaunchKernelGGL(k_radix_scatter, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, vals, shift,
                      (const uint32_t*)c->hist, (const uint32_t*)c->scan_tot, keys_out, vals_out);
 }

@@ -82,41 +82,49 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, c
 }
 
 // Destination offsets from the per-unit counts, in two small kernels.
-// k_radix_scan_cols: workgroup (segment s, digit group dg) turns the 16 columns hist[.][16 dg .. 16 dg + 15]
-// of the segment's units into exclusive prefixes down the column (16 threads per column, each walking
-// every 16th unit) and stores the column totals.  The exclusive scan over a segment's 256 totals is cheap
-// enough for every scattering wavefront to redo it for itself (wave_digit_bases), which saves a launch per
-// pass.  Offset of (unit u, digit d) = seg[s] + (totals of s before d) + hist[u][d].
-constexpr int kScanColThreads = 16;
+// k_radix_scan_cols: a workgroup takes 256 / LPC digit columns of one segment and turns each column
+// hist[.][digit] of the segment's units into exclusive prefixes down the column (LPC lanes per column, each
+// walking every LPC-th unit) and stores the column totals.  LPC = 16 suits the short segments of the key
+// passes (one trip for up to 256 units); a long segment (the pass over the application ids has a single one)
+// takes a whole wavefront per column, so that 1024 units are still one trip to memory.  The exclusive scan
+// over a segment's 256 totals is cheap enough for every scattering wavefront to redo it for itself
+// (wave_digit_bases), which saves a launch per pass.
+// Offset of (unit u, digit d) = seg[s] + (totals of s before d) + hist[u][d].
 constexpr int kScanUnroll = 16;
+constexpr int kSegTable = 1024;                        // applications whose tile prefixes k_segments keeps in LDS
 
+template <int LPC>
 __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* __restrict__ hist,
                                                          uint32_t* __restrict__ tot /*[nseg,256]*/) {
-  const int s = blockIdx.x / 16, dg = blockIdx.x % 16;
-  const int col = threadIdx.x / kScanColThreads, j = threadIdx.x % kScanColThreads;
-  const int dgt = dg * 16 + col;
+  constexpr int kCols = 256 / LPC;                       // digit columns per workgroup
+  constexpr int kGroups = 256 / kCols;                   // workgroups per segment
+  const int s = blockIdx.x / kGroups, dg = blockIdx.x % kGroups;
+  const int col = threadIdx.x / LPC, j = threadIdx.x % LPC;
+  const int dgt = dg * kCols + col;
   const int u0 = sp.unit_start[s], u1 = sp.unit_start[s + 1];
   uint32_t carry = 0;                                    // total of the column over the chunks done so far
   // kScanUnroll chunks per trip: their loads are independent of the carry and go out together, so a
-  // long column costs one memory round trip per kScanUnroll * 16 units instead of one per 16
-  for (int ub = u0; ub < u1; ub += kScanColThreads * kScanUnroll) {
+  // long column costs one memory round trip per kScanUnroll * LPC units instead of one per LPC
+  for (int ub = u0; ub < u1; ub += LPC * kScanUnroll) {
     uint32_t c[kScanUnroll];
 #pragma unroll
     for (int q = 0; q < kScanUnroll; ++q) {
-      const int u = ub + q * kScanColThreads + j;
+      const int u = ub + q * LPC + j;
       c[q] = u < u1 ? hist[(int64_t)u * 256 + dgt] : 0u;
     }
 #pragma unroll
     for (int q = 0; q < kScanUnroll; ++q) {
-      const int u = ub + q * kScanColThreads + j;
-      uint32_t incl = c[q];
+      const int u = ub + q * LPC + j;
+      if (ub + q * LPC < u1) {                           // uniform: the rest of the trip is past the segment
+        uint32_t incl = c[q];
 #pragma unroll
-      for (int o = 1; o < kScanColThreads; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, kScanColThreads);
-        if (j >= o) incl += up;
+        for (int o = 1; o < LPC; o <<= 1) {
+          const uint32_t up = __shfl_up(incl, o, LPC);
+          if (j >= o) incl += up;
+        }
+        if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c[q];
+        carry += __shfl(incl, LPC - 1, LPC);
       }
-      if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c[q];
-      carry += __shfl(incl, kScanColThreads - 1, kScanColThreads);
     }
   }
   if (j == 0) tot[(int64_t)s * 256 + dgt] = carry;
@@ -218,29 +226,72 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
     w.grp_end[a] = seg[a + 1];
   }
   if (threadIdx.x == 0) *w.grp_n = A;
-  if (threadIdx.x == 0) {
-    int ts = 0, us = 0;
-    for (int a = 0; a < A; ++a) {
-      tile_start[a] = ts;
-      unit_start[a] = us;
-      const int na = seg[a + 1] - seg[a];
-      ts += (na + tile - 1) / tile;
-      us += (na + unit - 1) / unit;
+  // prefixes of tiles and units over the applications: every thread takes a run of consecutive
+  // applications, the runs' totals are scanned across the workgroup (launched with 256 threads)
+  __shared__ int run_t[256], run_u[256];
+  __shared__ int s_tile[kSegTable + 1], s_seg[kSegTable + 1];   // used when A <= kSegTable
+  const int tid = threadIdx.x;
+  const int per = (A + 255) / 256;
+  const int a_lo = min(A, tid * per), a_hi = min(A, a_lo + per);
+  int ts = 0, us = 0;
+  for (int a = a_lo; a < a_hi; ++a) {
+    const int na = seg[a + 1] - seg[a];
+    ts += (na + tile - 1) / tile;
+    us += (na + unit - 1) / unit;
+  }
+  run_t[tid] = ts;
+  run_u[tid] = us;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const int t_up = tid >= o ? run_t[tid - o] : 0;
+    const int u_up = tid >= o ? run_u[tid - o] : 0;
+    __syncthreads();
+    run_t[tid] += t_up;
+    run_u[tid] += u_up;
+    __syncthreads();
+  }
+  const int ts0 = run_t[tid] - ts, us0 = run_u[tid] - us;   // exclusive prefixes of this thread's run
+  const bool table = A <= kSegTable;
+  ts = ts0;
+  us = us0;
+  for (int a = a_lo; a < a_hi; ++a) {
+    tile_start[a] = ts;
+    unit_start[a] = us;
+    const int sb = seg[a], na = seg[a + 1] - sb;
+    if (table) {
+      s_tile[a] = ts;
+      s_seg[a] = sb;
     }
-    tile_start[A] = ts;
-    unit_start[A] = us;
+    ts += (na + tile - 1) / tile;
+    us += (na + unit - 1) / unit;
+  }
+  if (tid == 255) {
+    tile_start[A] = run_t[255];
+    unit_start[A] = run_u[255];
+    if (table) {
+      s_tile[A] = run_t[255];
+      s_seg[A] = seg[A];
+    }
   }
   __syncthreads();
   // one descriptor per scoring tile, so that a scoring workgroup finds its place with a single load
-  if (A <= (int)blockDim.x) {
-    for (int a = 0; a < A; ++a) {
-      const int t0 = tile_start[a], nt = tile_start[a + 1] - t0, sb = seg[a], se = seg[a + 1];
-      for (int t = threadIdx.x; t < nt; t += blockDim.x) tile_desc[t0 + t] = make_int4(a, sb + t * tile, se, 0);
+  if (table) {
+    // few applications: every thread places tiles by searching the prefixes in LDS
+    const int n_tiles = s_tile[A];
+    for (int t = tid; t < n_tiles; t += 256) {
+      int lo = 0, hi = A;                                // last a with s_tile[a] <= t (empty applications share a start)
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (s_tile[mid] <= t) lo = mid; else hi = mid;
+      }
+      tile_desc[t] = make_int4(lo, s_seg[lo] + (t - s_tile[lo]) * tile, s_seg[lo + 1], 0);
     }
   } else {
-    for (int a = threadIdx.x; a < A; a += blockDim.x) {
-      const int t0 = tile_start[a], nt = tile_start[a + 1] - t0, sb = seg[a], se = seg[a + 1];
-      for (int t = 0; t < nt; ++t) tile_desc[t0 + t] = make_int4(a, sb + t * tile, se, 0);
+    ts = ts0;
+    for (int a = a_lo; a < a_hi; ++a) {
+      const int sb = seg[a], se = seg[a + 1], nt = (se - sb + tile - 1) / tile;
+      for (int t = 0; t < nt; ++t) tile_desc[ts + t] = make_int4(a, sb + t * tile, se, 0);
+      ts += nt;
     }
   }
 }
