@@ -564,3 +564,54 @@ def test_error_paths(gpu):
     rc, summ, _ = ctx.sp_schedule(0)
     assert rc == binding.SP_DONE and summ["n_scheduled"] + summ["n_dropped"] == 100
     ctx.close()
+
+
+def random_case(seed):
+    """A small workload, a policy and the optional profile extras, all drawn from the seed."""
+    rng = np.random.Generator(np.random.PCG64(7000 + seed))
+    A = int(rng.integers(1, 6))
+    classes = tuple(int(c) for c in np.where(rng.random(A) < 0.15, rng.integers(100, 300, A), rng.integers(2, 70, A)))
+    models = tuple(int(m) for m in rng.integers(1, 17, A))
+    head = ["logistic", "mlp_f32", "mlp_bf16", "logistic_bf16"][int(rng.integers(0, 4))]
+    bf16 = head.endswith("bf16")
+    wide = rng.random() < 0.12                      # beyond the widths the matrix-core kernels take
+    d = int(rng.integers(1, 6)) * 8 if bf16 else int(rng.integers(1, 41))
+    hidden = 0 if head.startswith("logistic") else int(rng.integers(3, 41))
+    if wide:
+        d = int(rng.integers(33, 41)) * 8
+        hidden = 0 if hidden == 0 else int(rng.integers(257, 300))
+    lo = float(rng.uniform(2.0, 20.0))
+    frac = rng.dirichlet(np.full(A, 2.0))
+    frac = tuple(float(f) for f in frac / frac.sum())
+    n = int(rng.integers(1, 1500)) if rng.random() < 0.6 else int(rng.integers(1500, 6000))
+    w = wl.tiny(seed=7100 + seed, n=n, classes=classes, models=models,
+                max_batch=int(rng.integers(1, 25)), feat_dim=d, hidden_dim=hidden,
+                feat_dtype=wl.BF16 if bf16 else wl.F32, penalty=int(rng.integers(0, 3)),
+                deadline=(lo, lo * float(rng.uniform(1.5, 12.0))), fractions=frac)
+    if rng.random() < 0.5:
+        wl.attach_priors(w.profile, seed=7200 + seed)
+    if rng.random() < 0.5:
+        wl.attach_swap_costs(w.profile, seed=7300 + seed, lo=0.2, hi=6.0, skip_every=int(rng.integers(0, 4)))
+    names = ["sneakpeek", "alg1", "lo_priority", "lo_edf", "maxacc_edf", "capped", "unit", "split", "split_alg1"]
+    name = names[int(rng.integers(0, len(names)))]
+    if name == "capped":
+        policy = wl.Policy(batch_cap=int(rng.integers(1, 9)))
+    elif name == "unit":
+        policy = wl.Policy(weight=wl.WEIGHT_UNIT, order=wl.ORDER_EDF if rng.random() < 0.5 else wl.ORDER_PRIORITY)
+    elif name.startswith("split"):
+        policy = copy.copy(wl.named_policy("alg1" if name == "split_alg1" else "sneakpeek"))
+        policy.split_groups = 1
+    else:
+        policy = wl.named_policy(name)
+    return w, policy, bf16, name
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_shapes_policies_and_profile_extras(gpu, seed):
+    """Random small workloads (ragged class / variant counts, every head kind and penalty, priors, swap-in
+    costs, every policy) through the whole path, against the oracle."""
+    w, policy, bf16, name = random_case(seed)
+    p = w.profile
+    print(f"seed {seed}: n={w.requests.n} classes={tuple(int(c) for c in p.n_classes)} models={tuple(int(m) for m in p.n_models)} "
+          f"B={p.max_batch} d={p.feat_dim} H={p.hidden_dim} bf16={bf16} policy={name}", flush=True)
+    full_parity(gpu, w, max_rounds=60, policy=policy, ea_tol=2e-3 if bf16 else None, want_cube=not bf16)
