@@ -615,3 +615,23 @@ def test_random_shapes_policies_and_profile_extras(gpu, seed):
     print(f"seed {seed}: n={w.requests.n} classes={tuple(int(c) for c in p.n_classes)} models={tuple(int(m) for m in p.n_models)} "
           f"B={p.max_batch} d={p.feat_dim} H={p.hidden_dim} bf16={bf16} policy={name}", flush=True)
     full_parity(gpu, w, max_rounds=60, policy=policy, ea_tol=2e-3 if bf16 else None, want_cube=not bf16)
+
+
+@pytest.mark.parametrize("d", [64, 65, 100, 128, 129, 201, 252, 256])
+def test_logistic_widths_of_the_matrix_core_kernel(gpu, d):
+    """Every padded feature width of the matrix-core logistic kernel (64, 128, 256), at and next to the
+    boundaries, with and without rows that are multiples of 16 bytes; several class tiles, a ragged last
+    class tile, several request tiles with a ragged tail."""
+    w = wl.tiny(seed=7400 + d, n=1100, classes=(70, 33, 5, 129), models=(3, 16, 1, 7), max_batch=9, feat_dim=d,
+                deadline=(5.0, 80.0), fractions=(0.45, 0.25, 0.05, 0.25))
+    wl.attach_priors(w.profile, seed=7500 + d, kinds=(None, "weak"))
+    full_parity(gpu, w, max_rounds=20, want_cube=True)
+
+
+@pytest.mark.parametrize("d,H", [(8, 3), (72, 33), (136, 128), (264, 200), (512, 256), (40, 255)])
+def test_bf16_mlp_widths_of_the_matrix_core_kernel(gpu, d, H):
+    """Input widths across the 64-channel slices of layer 1 (a ragged last slice included) and hidden widths
+    up to the kernel's 256."""
+    w = wl.tiny(seed=7600 + d, n=900, classes=(70, 33, 5), models=(3, 16, 1), max_batch=9, feat_dim=d, hidden_dim=H,
+                feat_dtype=wl.BF16, deadline=(5.0, 80.0), fractions=(0.5, 0.3, 0.2))
+    full_parity(gpu, w, max_rounds=20, ea_tol=2e-3)
