@@ -321,6 +321,11 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   if ((s = dev_alloc(c, &c->unit1, 2)) != SP_OK) return s;
   SP_HIP(c, hipHostMalloc((void**)&c->h_state, sizeof(State), hipHostMallocDefault));
   std::memset(c->h_state, 0, sizeof(State));
+  {
+    void* dp = nullptr;
+    SP_HIP(c, hipHostGetDevicePointer(&dp, c->h_state, 0));
+    c->w.st_host = (State*)dp;
+  }
   SP_HIP(c, hipMemset(w.st, 0, sizeof(State)));
   if ((s = setup_persist(c, p)) != SP_OK) return s;
   if (c->score_lds > 64 * 1024) {
@@ -596,8 +601,10 @@ void launch_round(sp_ctx* c, hipStream_t s, int32_t* ids_out, float* cube) {
     hipLaunchKernelGGL(k_round_commit, dim3(1), dim3(kRoundThreads), 0, s, c->tb, c->w, ids_out);
 }
 
-sp_status fetch_state(sp_ctx* c, hipStream_t s) {
-  SP_HIP(c, hipMemcpyAsync(c->h_state, c->w.st, sizeof(State), hipMemcpyDeviceToHost, s));
+// Brings the window state to the host.  mirrored: the last kernel on the stream was k_round_commit, which
+// has written the state into the pinned copy itself; otherwise it is copied here.
+sp_status fetch_state(sp_ctx* c, hipStream_t s, bool mirrored = false) {
+  if (!mirrored) SP_HIP(c, hipMemcpyAsync(c->h_state, c->w.st, sizeof(State), hipMemcpyDeviceToHost, s));
   SP_HIP(c, hipStreamSynchronize(s));
   SP_HIP(c, hipGetLastError());
   c->rounds_done = c->h_state->round;
@@ -765,7 +772,7 @@ sp_status sp_greedy_round(sp_ctx* c, void* stream, sp_decision* out_host, int32_
   hipStream_t s = (hipStream_t)stream;
   const int32_t before = c->rounds_done;
   launch_round(c, s, req_ids_out_dev, nullptr);
-  sp_status st = fetch_state(c, s);
+  sp_status st = fetch_state(c, s, true);
   if (st != SP_OK) return st;
   if (c->rounds_done == before) return SP_DONE;
   if (out_host) std::memcpy(out_host, &c->h_state->last, sizeof(sp_decision));

@@ -106,6 +106,7 @@ struct Window {
   int32_t log_cap;
   int32_t* last_ids;          // [B] members of the last committed batch
   State* st;
+  State* st_host;             // pinned host copy of *st that the two-kernel round path keeps current (device-visible address)
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

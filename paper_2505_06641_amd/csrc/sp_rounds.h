@@ -283,12 +283,26 @@ __device__ __forceinline__ void commit_members(const Tables& tb, const Window& w
   viol = block_sum_f64(viol, dsum);
 }
 
+// The window state as the host will read it after this kernel: written straight into pinned host memory by
+// the one thread that owns the state, so that a round per call needs no copy behind the kernel.
+__device__ __forceinline__ void mirror_state(const Window& w) {
+  if (w.st_host == nullptr) return;
+  const unsigned long long* src = reinterpret_cast<const unsigned long long*>(w.st);
+  unsigned long long* dst = reinterpret_cast<unsigned long long*>(w.st_host);
+  static_assert(sizeof(State) % 8 == 0, "State is copied in 8-byte words");
+#pragma unroll
+  for (int i = 0; i < (int)(sizeof(State) / 8); ++i) dst[i] = src[i];
+}
+
 __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Window w, int32_t* __restrict__ ids_out) {
   __shared__ unsigned long long red[kRoundThreads / 64];
   __shared__ double dsum[kRoundThreads];
   State* st = w.st;
-  if (st->done || st->err) return;
   const int tid = threadIdx.x;
+  if (st->done || st->err) {
+    if (tid == 0) mirror_state(w);
+    return;
+  }
   unsigned long long best = 0ull;
   const int n_cand = *w.grp_n * tb.Mmax;
   for (int i = tid; i < n_cand; i += kRoundThreads) {
@@ -297,7 +311,10 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
   }
   best = block_max_u64(best, red);
   if (best == 0ull) {                 // nothing live anywhere
-    if (tid == 0) st->done = 1;
+    if (tid == 0) {
+      st->done = 1;
+      mirror_state(w);
+    }
     return;
   }
   if (tb.pol_group_first) {
@@ -347,6 +364,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
     st->total_wu += wu;
     st->total_u += su;
     st->total_viol += viol;
+    mirror_state(w);
   }
 }
 
