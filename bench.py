@@ -220,6 +220,16 @@ def main():
         roof = {"bound": "mfma" if (split or mlp_mfma) else "alu", "achieved": tflops, "peak": peak_c, "unit": "TFLOP/s", "frac": tflops / peak_c}
     else:
         roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    if split or mlp_mfma:
+        # what the matrix cores sustain on this device, measured now: the bare half-precision MFMA loop on
+        # constant operands and on operands with random bits (the clock drops with the toggle rate, so the
+        # second figure is the ceiling for real data); the kernel's ceiling scaled by sustained / published
+        tf_const, ghz_const = binding.sp_debug_mfma_rate(False)
+        tf_rand, ghz_rand = binding.sp_debug_mfma_rate(True)
+        sustained = peak_c * tf_rand / PEAK_MFMA_F16_TFLOPS
+        roof["mfma_f16_measured"] = {"constant_operands_tflops": tf_const, "constant_operands_clock_ghz": ghz_const,
+                                     "random_operands_tflops": tf_rand, "random_operands_clock_ghz": ghz_rand,
+                                     "peak_scaled_to_random_operands": sustained, "frac_of_that": tflops / sustained}
     roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": measured_traffic(args.workload),
                  "peak_note": peak_note, "x_fp32_mfma_peak": tflops / PEAK_MFMA_F32_TFLOPS,
                  "algorithmic_flops": flops, "algorithmic_bytes": k_bytes, "hbm_gbs": gbs, "tflops": tflops})

@@ -284,6 +284,20 @@ int32_t sp_max_classes(const sp_ctx* ctx);
  * per round.  The decisions are the same either way.  sp_greedy_round always takes the second way. */
 int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 
+/*
+ * Diagnostic, not on the hot path: the rate at which the device's matrix cores run the half-precision
+ * instruction the scoring kernel is built on (posterior of Def. 4.1.2 and the contraction of Sec. 4.1
+ * eq. (9)) when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.
+ * The clock the device sustains depends on how many operand bits toggle, so the second figure is the
+ * ceiling a kernel fed with real data can reach.  iters in [1, 2^20]: instructions per wavefront = 8 * iters
+ * (2048 wavefronts, two per SIMD).  stream: a hipStream_t.  tflops_out (HOST, required): 2 * 32 * 32 * 16 flops per
+ * instruction over the time of one launch between two events; clock_ghz_out (HOST, may be NULL): shader
+ * cycles over the constant-rate counter.  Allocates and frees its own small buffers; synchronises the stream.
+ * SP_EINVAL: iters out of range or tflops_out NULL; SP_EDEVICE: no such device or a HIP call failed.
+ */
+sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, void* stream, double* tflops_out,
+                             double* clock_ghz_out);
+
 #ifdef __cplusplus
 }
 #endif

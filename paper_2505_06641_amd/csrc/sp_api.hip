@@ -17,6 +17,7 @@
 #include "sp_score_mlp.h"
 #include "sp_rounds_persist.h"
 #include "sp_sort.h"
+#include "sp_probe.h"
 
 using namespace sp;
 
@@ -1036,5 +1037,42 @@ sp_status sp_set_swap_cost(sp_ctx* c, int32_t app, const float* swap_ms_host) {
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
 int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist && !c->tb.pol_split) ? 1 : 0; }
+
+sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, void* stream, double* tflops_out,
+                             double* clock_ghz_out) {
+  if (iters < 1 || iters > (1 << 20) || !tflops_out) return SP_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) return SP_EDEVICE;
+  DeviceGuard g(device_id);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  float* out = nullptr;
+  long long* clk = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  sp_status rc = SP_EDEVICE;
+  float ms = 0.f;
+  long long h[2] = {0, 0};
+  if (hipMalloc((void**)&out, (size_t)kProbeBlocks * kProbeThreads * sizeof(float)) != hipSuccess) goto end;
+  if (hipMalloc((void**)&clk, 2 * sizeof(long long)) != hipSuccess) goto end;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto end;
+  // one untimed launch brings the clocks up, the second is timed
+  hipLaunchKernelGGL(k_mfma_rate, dim3(kProbeBlocks), dim3(kProbeThreads), 0, s, (int)random_bits, (int)iters, out, clk);
+  if (hipEventRecord(e0, s) != hipSuccess) goto end;
+  hipLaunchKernelGGL(k_mfma_rate, dim3(kProbeBlocks), dim3(kProbeThreads), 0, s, (int)random_bits, (int)iters, out, clk);
+  if (hipEventRecord(e1, s) != hipSuccess) goto end;
+  if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) goto end;
+  if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) goto end;
+  if (hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) goto end;
+  // 2 * 32 * 32 * 16 flops per instruction and wavefront
+  *tflops_out = (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * kProbeMfmaPerIter * 32768.0 / ((double)ms * 1e-3) / 1e12;
+  if (clock_ghz_out) *clock_ghz_out = h[1] > 0 ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
+  rc = SP_OK;
+end:
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (out) (void)hipFree(out);
+  if (clk) (void)hipFree(clk);
+  return rc;
+}
 
 }  // extern "C"

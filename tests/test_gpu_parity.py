@@ -635,3 +635,17 @@ def test_bf16_mlp_widths_of_the_matrix_core_kernel(gpu, d, H):
     w = wl.tiny(seed=7600 + d, n=900, classes=(70, 33, 5), models=(3, 16, 1), max_batch=9, feat_dim=d, hidden_dim=H,
                 feat_dtype=wl.BF16, deadline=(5.0, 80.0), fractions=(0.5, 0.3, 0.2))
     full_parity(gpu, w, max_rounds=20, ea_tol=2e-3)
+
+
+def test_matrix_core_rate_diagnostic(gpu):
+    torch, binding = gpu
+    tf_c, ghz_c = binding.sp_debug_mfma_rate(False, iters=2048)
+    tf_r, ghz_r = binding.sp_debug_mfma_rate(True, iters=2048)
+    # one instruction per 32 cycles and SIMD: rate and clock must agree (2048 wavefronts on 1024 SIMDs)
+    for tf, ghz in ((tf_c, ghz_c), (tf_r, ghz_r)):
+        assert 100.0 < tf < 2600.0 and 0.5 < ghz < 3.0
+        assert tf == pytest.approx(1024 * 32768 / 32 * ghz * 1e9 / 1e12, rel=0.15)
+    assert tf_r <= tf_c * 1.1
+    with pytest.raises(binding.SneakPeekError) as e:
+        binding.sp_debug_mfma_rate(True, iters=0)
+    assert e.value.status == binding.SP_EINVAL
