@@ -140,27 +140,26 @@ __device__ __forceinline__ float one_minus_penalty(int kind, float D, float invD
 // Same quantity with the completion time given as an unevaluated float pair E = e_hi + e_lo
 // (e_hi = float(E), e_lo = float(E - e_hi)), for inner loops that should stay in float32; the penalty
 // kind is a template parameter so that those loops carry no branches.
-// l = (e_hi - D) + e_lo and r = (2D - e_hi) - e_lo: where E and D (or 2D) are within a factor two of
-// each other the first difference is exact (Sterbenz), so l and r carry E's full precision exactly
-// where cancellation would hurt; elsewhere their relative error is one rounding.  A rounded sum has
-// the sign of the exact sum, so l <= 0 (on time) and r <= 0 (penalty 1) are decided exactly as in
-// double precision.  The sigmoid's denominator x^3 + y^3 is at least 1/4 (x + y = 1), so the
-// hardware reciprocal (1 ulp) is safe.
+// Step: l = (e_hi - D) + e_lo; a rounded sum has the sign of the exact sum, so l <= 0 (on time) is decided
+// exactly as in double precision.  Linear and sigmoid: r = (2D - e_hi) - e_lo; where E and 2D are within a
+// factor two of each other the first difference is exact (Sterbenz), so r carries E's full precision
+// exactly where cancellation would hurt, elsewhere its relative error is one rounding.  y = r / D clamped
+// to [0, 1] is 1 when the request is on time and 0 once the penalty has reached 1, and both penalties are
+// continuous there, so no comparison is needed: linear 1 - gamma = y; sigmoid y^3 / (x^3 + y^3) with
+// x = 1 - y (exact for y >= 1/2; below that x is near 1 and one rounding is harmless).  The denominator is
+// at least 1/4, so the hardware reciprocal (1 ulp) is safe.
 template <int KIND>
 __device__ __forceinline__ float one_minus_penalty_f32(float D, float twoD, float invD, float e_hi, float e_lo) {
-  const float l = (e_hi - D) + e_lo;
-  if (KIND == 0) return l <= 0.f ? 1.0f : 0.f;
-  const float r = (twoD - e_hi) - e_lo;
-  float v;
-  if (KIND == 1) {
-    v = r * invD;
-  } else {
-    const float x = l * invD, y = r * invD;
-    const float y3 = y * y * y, x3 = x * x * x;
-    v = y3 * __builtin_amdgcn_rcpf(x3 + y3);
+  if (KIND == 0) {
+    const float l = (e_hi - D) + e_lo;
+    return l <= 0.f ? 1.0f : 0.f;
   }
-  v = r <= 0.f ? 0.f : v;
-  return l <= 0.f ? 1.0f : v;
+  const float r = (twoD - e_hi) - e_lo;
+  const float y = __builtin_amdgcn_fmed3f(r * invD, 0.f, 1.f);
+  if (KIND == 1) return y;
+  const float x = 1.0f - y;
+  const float y3 = y * y * y, x3 = x * x * x;
+  return y3 * __builtin_amdgcn_rcpf(x3 + y3);
 }
 
 // dead: penalty already 1 on the earliest possible completion E0.
