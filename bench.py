@@ -36,8 +36,8 @@ PEAK_VALU_F32_TFLOPS = 157.3
 KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
 MEASURED_TRAFFIC = {
     # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
-    "cfg5": (1524.27e6 + 110.47e6, "af3d9506d399bcca785972b4e2fb984a6175b122ea2a26ade8e98c5b1daed9b1"),
-    "cfg4": (95.00e6 + 3.20e6, "af3d9506d399bcca785972b4e2fb984a6175b122ea2a26ade8e98c5b1daed9b1"),
+    "cfg5": (1522.54e6 + 109.89e6, "1dbfc626e6fc4df0a7c599f08a6ec3c2c5c47eee0ab622638c2b68e695e38755"),
+    "cfg4": (95.00e6 + 3.20e6, "1dbfc626e6fc4df0a7c599f08a6ec3c2c5c47eee0ab622638c2b68e695e38755"),
 }
 
 
