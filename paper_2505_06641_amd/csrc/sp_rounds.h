@@ -20,14 +20,16 @@
 namespace sp {
 
 constexpr int kRoundThreads = 512;
+constexpr int kSmallGroup = 256;                  // remaining range up to which one wavefront scores a subgroup
 constexpr int kPairLanes = 8;                       // lanes that share one pair of batch sizes in the triangle
 
-__device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
+// nthr: the threads of the workgroup that are still running (a power of two; the others have left).
+__device__ __forceinline__ double block_sum_f64(double v, double* scratch, int nthr = kRoundThreads) {
   // fixed-order tree: the result does not depend on scheduling
   __syncthreads();
   scratch[threadIdx.x] = v;
   __syncthreads();
-  for (int o = kRoundThreads / 2; o > 0; o >>= 1) {
+  for (int o = nthr / 2; o > 0; o >>= 1) {
     if ((int)threadIdx.x < o) scratch[threadIdx.x] += scratch[threadIdx.x + o];
     __syncthreads();
   }
@@ -45,7 +47,8 @@ __device__ __forceinline__ unsigned long long pack_candidate(float score, uint32
   return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - cand_id);
 }
 
-__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* scratch) {
+__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* scratch,
+                                                           int nwaves = 0 /* 0: the whole workgroup */) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const unsigned long long other = __shfl_xor(v, o);
@@ -56,7 +59,8 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
   if (lane == 0) scratch[wave] = v;
   __syncthreads();
   unsigned long long r = scratch[0];
-  for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = scratch[i] > r ? scratch[i] : r;
+  if (nwaves == 0) nwaves = (int)(blockDim.x >> 6);
+  for (int i = 1; i < nwaves; ++i) r = scratch[i] > r ? scratch[i] : r;
   return r;
 }
 
@@ -68,12 +72,13 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 // Every kernel that scores rounds calls this function: their scores agree bit for bit.
 template <int KIND>
 __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* ent, const float* lat, int nb, int B,
-                                                                double t, uint32_t cid0, float* cube_out, int only_b) {
+                                                                double t, uint32_t cid0, float* cube_out, int only_b,
+                                                                int nthr) {
   const int tid = threadIdx.x;
   const int sub = tid % kPairLanes, grp = tid / kPairLanes;
   const int n_pairs = (B + 1) / 2;
   unsigned long long best = 0ull;
-  for (int p = grp; p < n_pairs; p += kRoundThreads / kPairLanes) {
+  for (int p = grp; p < n_pairs; p += nthr / kPairLanes) {
     const int b1 = p + 1, b2 = B - p;                 // b1 <= b2; equal for the middle size of an odd B
     const double E1 = t + (double)lat[b1 - 1], E2 = t + (double)lat[b2 - 1];
     const float e1h = (float)E1, e1l = (float)(E1 - (double)e1h);
@@ -123,11 +128,14 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
   return best;
 }
 
+// nthr: the threads taking part (a multiple of 64).  A score is summed by the same kPairLanes lanes in the
+// same order however many take part, so the result does not depend on it.
 __device__ __forceinline__ unsigned long long triangle_best(int kind, const float4* ent, const float* lat, int nb, int B,
-                                                           double t, uint32_t cid0, float* cube_out, int only_b) {
-  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b);
-  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b);
-  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b);
+                                                           double t, uint32_t cid0, float* cube_out, int only_b,
+                                                           int nthr = kRoundThreads) {
+  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
+  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
+  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
 }
 
 // Penalty kind the candidates of application a are compared under: its own (eq. 13), or the step penalty
@@ -176,6 +184,11 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   const double E0 = t + (double)tb.lmin[a];
   const int seg_e = w.grp_end[grp];
   const int head = w.head[(r & 1) * w.gcap + grp];
+  // With the requests split into subgroups (Sec. 5.3.2) most groups hold a handful of requests: one
+  // wavefront then does the whole workgroup's job and the others leave (a barrier counts only the
+  // wavefronts that are still running).
+  const int nthr = (tb.pol_split && seg_e - head <= kSmallGroup) ? 64 : kRoundThreads;
+  if (tid >= nthr) return;
 
   // ---- candidate window: first B live requests in service order ----
   // The first step looks at 4 positions per thread (1024 per workgroup, enough while most of the queue
@@ -212,7 +225,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     if (lane == 63) wave_cnt[wave] = incl;
     __syncthreads();
     int before = found, total = found;
-    for (int i = 0; i < kRoundThreads / 64; ++i) {
+    for (int i = 0; i < nthr / 64; ++i) {
       if (i < wave) before += wave_cnt[i];
       total += wave_cnt[i];
     }
@@ -224,12 +237,12 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
       win[rank++] = p0 + j;
     }
     found = total;
-    base += 4 * nq * kRoundThreads;
+    base += 4 * nq * nthr;
     __syncthreads();
   }
   const int nb = min(found, Bw);
   if (m == 0) {
-    for (int j = tid; j < nb; j += kRoundThreads) w.win_pos[grp * B + j] = win[j];
+    for (int j = tid; j < nb; j += nthr) w.win_pos[grp * B + j] = win[j];
     if (tid == 0) {
       w.win_n[grp] = nb;
       w.head[((r + 1) & 1) * w.gcap + grp] = nb > 0 ? win[0] : seg_e;
@@ -239,18 +252,20 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     if (tid == 0) w.cand[blockIdx.x] = 0ull;
     return;
   }
-  for (int j = tid; j < nb; j += kRoundThreads) ent[j] = window_entry(tb, w, win[j], m);
+  for (int j = tid; j < nb; j += nthr) ent[j] = window_entry(tb, w, win[j], m);
   __syncthreads();
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
   const double t0 = start_time(tb, st->last, t, a, m);
   unsigned long long best = triangle_best(scoring_penalty(tb, kind), ent, lat, nb, Bw, t0,
-                                          (uint32_t)((grp * tb.Mmax + m) * B), cube_out, tb.pol_whole ? nb : 0);
+                                          (uint32_t)((grp * tb.Mmax + m) * B), cube_out, tb.pol_whole ? nb : 0, nthr);
   if (tb.pol_group_first) {
     // the group's priority (eq. 14) over the window; the same fixed-order sum in every kernel that forms it
-    const double ps = block_sum_f64(tid < nb ? (double)ordering_value(tb, w, win[tid]) : 0.0, dsum);
+    double part = 0.0;                                   // one term per thread when the whole workgroup runs
+    for (int j = tid; j < nb; j += nthr) part += (double)ordering_value(tb, w, win[j]);
+    const double ps = block_sum_f64(part, dsum, nthr);
     if (tid == 0) w.cand_prio[blockIdx.x] = (float)(ps / (double)nb);
   }
-  best = block_max_u64(best, red);
+  best = block_max_u64(best, red, nthr / 64);
   if (tid == 0) w.cand[blockIdx.x] = best;
 }
 
