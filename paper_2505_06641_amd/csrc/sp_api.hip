@@ -130,7 +130,7 @@ sp_status dev_upload(sp_ctx* c, T** out, const std::vector<T>& host) {
 int unit_size_for(int64_t n) {
   int64_t s = ((n / 2048 + 63) / 64) * 64;
   if (s < 256) s = 256;
-  if (s > 1024) s = 1024;
+  if (s > kMaxUnit) s = kMaxUnit;
   return (int)s;
 }
 

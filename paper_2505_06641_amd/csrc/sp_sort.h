@@ -20,6 +20,7 @@
 namespace sp {
 
 constexpr int kSortWaves = 4;
+constexpr int kMaxUnit = 1024;                  // largest sort unit (elements per wavefront and pass)
 
 struct SortPlan {
   const int32_t* seg;          // [nseg+1] segment starts
@@ -75,7 +76,15 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, c
   int beg = 0, end = 0;
   const bool have = unit_range(sp, u, beg, end);
   if (have) {
-    for (int i = beg + lane; i < end; i += 64) atomicAdd(&cnt[wave][(keys[i] >> shift) & 255u], 1u);
+    uint32_t kbuf[kMaxUnit / 64];                          // all of the unit's keys in flight together
+#pragma unroll
+    for (int c = 0; c < kMaxUnit / 64; ++c) {
+      const int i = beg + c * 64 + lane;
+      kbuf[c] = i < end ? keys[i] : 0u;
+    }
+#pragma unroll
+    for (int c = 0; c < kMaxUnit / 64; ++c)
+      if (beg + c * 64 + lane < end) atomicAdd(&cnt[wave][(kbuf[c] >> shift) & 255u], 1u);
     wave_sync();
     for (int i = lane; i < 256; i += 64) hist[(int64_t)u * 256 + i] = cnt[wave][i];
   }
@@ -168,11 +177,23 @@ __global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
   }
   wave_sync();
   const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int base = beg; base < end; base += 64) {
-    const int i = base + lane;
+  // the whole unit's keys and values are requested before the first one is used: one trip to memory per
+  // unit instead of one per 64 elements (the ranking below is a dependent chain through LDS)
+  uint32_t kbuf[kMaxUnit / 64];
+  int32_t vbuf[kMaxUnit / 64];
+#pragma unroll
+  for (int c = 0; c < kMaxUnit / 64; ++c) {
+    const int i = beg + c * 64 + lane;
+    kbuf[c] = i < end ? keys_in[i] : 0u;
+    vbuf[c] = i < end ? (vals_in ? vals_in[i] : i) : 0;
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxUnit / 64; ++c) {
+    if (beg + c * 64 >= end) break;                        // uniform
+    const int i = beg + c * 64 + lane;
     const bool valid = i < end;
-    const uint32_t key = valid ? keys_in[i] : 0u;
-    const int32_t val = valid ? (vals_in ? vals_in[i] : i) : 0;
+    const uint32_t key = kbuf[c];
+    const int32_t val = vbuf[c];
     const uint32_t dg = (key >> shift) & 255u;
     const unsigned long long same = match_digit(dg, valid);
     const int rank = __popcll(same & lt);
