@@ -127,8 +127,11 @@ sp_status dev_upload(sp_ctx* c, T** out, const std::vector<T>& host) {
   return SP_OK;
 }
 
+// Elements per sort unit (one wavefront per unit and pass): about a thousand units, between 256 and
+// kMaxUnit elements each.  Larger units mean fewer rows for the column scans, which is what the passes
+// spend most of their time on at these sizes; smaller ones only pay below a few hundred thousand requests.
 int unit_size_for(int64_t n) {
-  int64_t s = ((n / 2048 + 63) / 64) * 64;
+  int64_t s = ((n / 1024 + 63) / 64) * 64;
   if (s < 256) s = 256;
   if (s > kMaxUnit) s = kMaxUnit;
   return (int)s;
@@ -313,8 +316,7 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   for (int i = 0; i < 3; ++i)
     if ((s = dev_alloc(c, &c->bufV[i], N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.id_s, N)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &w.D_g, N)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &w.w_g, N)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.rec_g, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &c->scan_tot, (size_t)(A + 1) * 256)) != SP_OK) return s;
   c->hist_units = (int64_t)std::max<size_t>(2048, N / 256) + A + 8;
   if ((s = dev_alloc(c, &c->hist, (size_t)c->hist_units * 256)) != SP_OK) return s;
@@ -738,7 +740,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       }
     }
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
-                       (const uint32_t*)k_in, (const int32_t*)curV, w, c->tb.pol_edf | c->tb.pol_split);
+                       (const uint32_t*)k_in, w, c->tb.pol_edf | c->tb.pol_split);
     if (c->tb.pol_split) {
       hipLaunchKernelGGL(k_slot_ranges, dim3((c->n_slots + 255) / 256), dim3(256), 0, s, c->n_slots,
                          (const int32_t*)c->slot_app, (const int32_t*)c->slot_base, (const int32_t*)w.seg,

@@ -79,8 +79,7 @@ struct Window {
   int32_t* unit_start;        // [A+1] prefix of sort units
   float* ea;                  // [n, Mmax]
   float* key;                 // [n]
-  float* D_g;                 // [n] deadline at each position of the application-grouped (pre-order) array
-  float* w_g;                 // [n] weight, same indexing
+  float4* rec_g;              // [n] (request id bits, deadline, weight, 0) at each position of the application-grouped (pre-order) array
   int32_t* id_s;              // [n] request id at each service position
   float* D_s;                 // [n]
   float* w_s;                 // [n]

@@ -398,8 +398,7 @@ __device__ __forceinline__ void score_epilogue(const Tables& tb, const Window& w
     const float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
     w.key[id] = key;
     sortkey[pos] = tb.pol_edf ? __float_as_uint(Di) : ~__float_as_uint(key);   // ascending deadline, or descending key
-    w.D_g[pos] = Di;
-    w.w_g[pos] = wi;
+    w.rec_g[pos] = make_float4(__int_as_float(id), Di, wi, 0.f);   // what the ordering needs of this request, in one piece
   }
 }
 

@@ -398,21 +398,22 @@ __global__ void k_copy_outputs(int n, Window w, int32_t* __restrict__ model, int
 }
 
 // After the last pass.  The passes carried positions of the application-grouped array as values and the
-// inverted key bits as keys, so per service position: id, deadline and weight are gathers from the
-// grouped arrays (local to the application's range), the key comes straight from the sorted key bits.
+// inverted key bits as keys, so per service position: id, deadline and weight come with one gather of the
+// record the scoring kernel left at the grouped position, the key straight from the sorted key bits.
 __global__ void k_finish_order(int n, int n_valid_at /*index into seg*/, const int32_t* __restrict__ seg,
                                const int32_t* __restrict__ grouped_pos, const uint32_t* __restrict__ sorted_keys,
-                               const int32_t* __restrict__ ids_grouped, Window w, int edf) {
+                               Window w, int edf) {
   const int pos = blockIdx.x * blockDim.x + threadIdx.x;
   if (pos >= n) return;
   const int nv = seg[n_valid_at];
   if (pos < nv) {
-    const int gp = grouped_pos[pos];
-    w.id_s[pos] = ids_grouped[gp];
-    w.D_s[pos] = w.D_g[gp];
-    w.w_s[pos] = w.w_g[gp];
+    const float4 rc = w.rec_g[grouped_pos[pos]];          // one 16-byte gather per request
+    const int id = __float_as_int(rc.x);
+    w.id_s[pos] = id;
+    w.D_s[pos] = rc.y;
+    w.w_s[pos] = rc.z;
     // the passes sorted the inverted key bits, or (earliest deadline first) the deadline bits
-    w.key_s[pos] = edf ? w.key[ids_grouped[gp]] : __uint_as_float(~sorted_keys[pos]);
+    w.key_s[pos] = edf ? w.key[id] : __uint_as_float(~sorted_keys[pos]);
     w.alive_s[pos] = 1;
   } else {
     w.alive_s[pos] = 0;
