@@ -36,8 +36,8 @@ PEAK_VALU_F32_TFLOPS = 157.3
 KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
 MEASURED_TRAFFIC = {
     # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
-    "cfg5": (1522.54e6 + 109.89e6, "1dbfc626e6fc4df0a7c599f08a6ec3c2c5c47eee0ab622638c2b68e695e38755"),
-    "cfg4": (95.00e6 + 3.20e6, "1dbfc626e6fc4df0a7c599f08a6ec3c2c5c47eee0ab622638c2b68e695e38755"),
+    "cfg5": (1523.14e6 + 118.77e6, "6a9aade9ce9c15cbdcb8f880991fb43a23b305d462fb6321b7060a25d2480cb2"),
+    "cfg4": (95.00e6 + 3.73e6, "6a9aade9ce9c15cbdcb8f880991fb43a23b305d462fb6321b7060a25d2480cb2"),
 }
 
 
