@@ -16,6 +16,7 @@
 // pending flags, appends the decision to the log and advances the clock.
 #pragma once
 #include "sp_common.h"
+#include "sp_wave.h"
 
 namespace sp {
 
@@ -216,12 +217,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     }
     // exclusive prefix of the per-thread counts over the workgroup
     const int cnt = __popc(mask);
-    int incl = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
-    }
+    const int incl = (int)wave_scan_incl((uint32_t)cnt);
     if (lane == 63) wave_cnt[wave] = incl;
     __syncthreads();
     int before = found, total = found;

@@ -313,12 +313,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
           }
         }
         const int cnt = __popc(mask);
-        int incl = cnt;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int up = __shfl_up(incl, o);
-          if (lane >= o) incl += up;
-        }
+        const int incl = (int)wave_scan_incl((uint32_t)cnt);
         if (lane == 63) wave_cnt[wave] = incl;
         __syncthreads();
         int before = nb, total = nb;

@@ -15,6 +15,7 @@
 // wavefront-private running offset table in LDS.  No inter-workgroup waiting.
 #pragma once
 #include "sp_common.h"
+#include "sp_wave.h"
 #include "sp_score_generic.h"   // find_segment
 
 namespace sp {
@@ -105,6 +106,7 @@ constexpr int kSegTable = 1024;                        // applications whose til
 template <int LPC>
 __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* __restrict__ hist,
                                                          uint32_t* __restrict__ tot /*[nseg,256]*/) {
+  static_assert(LPC == 16 || LPC == 64, "a column is scanned by a row of 16 lanes or by a wavefront");
   constexpr int kCols = 256 / LPC;                       // digit columns per workgroup
   constexpr int kGroups = 256 / kCols;                   // workgroups per segment
   const int s = blockIdx.x / kGroups, dg = blockIdx.x % kGroups;
@@ -125,12 +127,7 @@ __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* 
     for (int q = 0; q < kScanUnroll; ++q) {
       const int u = ub + q * LPC + j;
       if (ub + q * LPC < u1) {                           // uniform: the rest of the trip is past the segment
-        uint32_t incl = c[q];
-#pragma unroll
-        for (int o = 1; o < LPC; o <<= 1) {
-          const uint32_t up = __shfl_up(incl, o, LPC);
-          if (j >= o) incl += up;
-        }
+        const uint32_t incl = wave_scan_incl<LPC == 16>(c[q]);   // LPC lanes per column: a row, or the wavefront
         if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c[q];
         carry += __shfl(incl, LPC - 1, LPC);
       }
@@ -144,12 +141,7 @@ __global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* 
 __device__ __forceinline__ uint4 wave_digit_bases(const uint32_t* __restrict__ tot_s, uint32_t seg_start, int lane) {
   const uint4 t = *reinterpret_cast<const uint4*>(tot_s + 4 * lane);
   const uint32_t mine = t.x + t.y + t.z + t.w;
-  uint32_t incl = mine;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
+  const uint32_t incl = wave_scan_incl(mine);
   uint4 b;
   b.x = seg_start + incl - mine;
   b.y = b.x + t.x;
