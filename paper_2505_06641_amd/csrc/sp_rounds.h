@@ -50,11 +50,7 @@ __device__ __forceinline__ unsigned long long pack_candidate(float score, uint32
 
 __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* scratch,
                                                            int nwaves = 0 /* 0: the whole workgroup */) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const unsigned long long other = __shfl_xor(v, o);
-    v = other > v ? other : v;
-  }
+  v = wave_max_u64(v);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
   if (lane == 0) scratch[wave] = v;
@@ -108,11 +104,9 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
       s2 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e2h, e2l);
     }
     s2 += s3;
-#pragma unroll
-    for (int o = 1; o < kPairLanes; o <<= 1) {
-      s1 += __shfl_xor(s1, o);
-      s2 += __shfl_xor(s2, o);
-    }
+    static_assert(kPairLanes == 8, "sum8 adds over groups of 8 lanes");
+    s1 = sum8(s1);
+    s2 = sum8(s2);
     if (sub == 0) {
       if (n1 > 0) {
         const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
