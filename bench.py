@@ -36,8 +36,8 @@ PEAK_VALU_F32_TFLOPS = 157.3
 KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
 MEASURED_TRAFFIC = {
     # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
-    "cfg5": (1523.14e6 + 118.77e6, "6a9aade9ce9c15cbdcb8f880991fb43a23b305d462fb6321b7060a25d2480cb2"),
-    "cfg4": (95.00e6 + 3.73e6, "6a9aade9ce9c15cbdcb8f880991fb43a23b305d462fb6321b7060a25d2480cb2"),
+    "cfg5": (1506.15e6 + 118.57e6, "cad75f14d2cebdec99f48bef117ba5e06a06f0b4ba350a521ba7d9f7f95884a6"),
+    "cfg4": (94.48e6 + 3.73e6, "cad75f14d2cebdec99f48bef117ba5e06a06f0b4ba350a521ba7d9f7f95884a6"),
 }
 
 

@@ -16,11 +16,15 @@
 // (classes on the MFMA row axis: every lane owns one request column and 16 of
 // the 32 classes, so softmax statistics stay inside a lane), keeps a running
 // maximum per request (online softmax), splits the exponentials the same way
-// and feeds them back into the matrix cores against a [17 x 32] table tile
-// (the variants' per-class accuracies plus a row of ones): rows 0..15
-// accumulate sum_c exp(z_c) Acc[m][c], row 16 accumulates sum_c exp(z_c).  The
-// posterior is never formed or stored (Def. 4.1.2; Sec. 4.1 eq. (9)); EA =
-// rows 0..15 / row 16, then variance and key (Sec. 5.1.1 eq. (12)).
+// and feeds them back into the matrix cores against the [16 x 32] tile of the
+// variants' per-class accuracies on v_mfma_f32_16x16x32_f16 (16 variants x 16
+// requests x 32 classes per instruction, half the matrix-core time of a 32-row
+// tile whose upper half would be empty; one exchange of lane rows puts the
+// exponentials where that instruction reads them), accumulating
+// sum_c exp(z_c) Acc[m][c]; the denominator sum_c exp(z_c) is a plain sum in
+// the lanes.  The posterior is never formed or stored (Def. 4.1.2; Sec. 4.1
+// eq. (9)); EA = numerators / denominator, then variance and key (Sec. 5.1.1
+// eq. (12)).
 //
 // Weights, table and bias of each (application, class tile) are packed once at
 // context creation into one contiguous block in exactly the order the lanes
@@ -48,13 +52,15 @@ constexpr float kExpShift = 14.0f;          // exponentials are scaled into (0, 
 // Packed block of one (application, class tile), in 16-byte units (8 halves or 4 floats each):
 //   W     [D/16][2][64]  unit ((s*2 + part)*64 + lane): halves e = 0..7 hold part (0 = hi, 1 = lo) of
 //                        W'[k = (lane/32)*D/2 + 8 s + e][class = 32 ct + lane%32], W' = W * 2^ew
-//   table [2][2][64]     unit ((ks*2 + part)*64 + lane): halves e hold part of T[m = lane%32][class], class =
-//                        32 ct + 8 (2 ks + e/4) + 4 (lane/32) + e%4; T = Acc (m < M), 1 (m = 16), else 0
+//   table [2][64]        unit (part*64 + lane): halves e hold part of Acc[m = lane%16][class] (0 for m >= M),
+//                        class = 32 ct + 16 s + 8 (e/4) + 4 g + e%4 with g = lane/32, s = (lane/16)%2: the
+//                        A operand of a 16x16x32 MFMA whose K index 8 (lane/16) + e runs over the classes
+//                        in the order the exponentials sit in the lanes after the row swap (softmax_phase)
 //   bias  [4][2]         unit (q*2 + g): floats j = 0..3 hold b[32 ct + 8 q + 4 g + j], -1e30 beyond C
 template <int D>
 struct SplitBlock {
   static constexpr int kWUnits = (D / 16) * 2 * 64;
-  static constexpr int kTabUnits = 2 * 2 * 64;
+  static constexpr int kTabUnits = 2 * 64;
   static constexpr int kBiasUnits = 8;
   static constexpr int kChunks = (kWUnits + kTabUnits + kBiasUnits + 63) / 64;   // 1 KB pieces, one LDS-DMA each
   static constexpr int kUnits = kChunks * 64;
@@ -114,17 +120,16 @@ inline float pack_split_blocks(const float* W /*[d,C]*/, const float* b /*[C]*/,
           wh[((size_t)(s * 2 + 1) * 64 + lane) * 8 + e] = lo;
         }
     uint16_t* tab = wh + (size_t)SB::kWUnits * 8;
-    for (int ks = 0; ks < 2; ++ks)
-      for (int lane = 0; lane < 64; ++lane)
-        for (int e = 0; e < 8; ++e) {
-          const int m = lane % 32, cls = 32 * ct + 8 * (2 * ks + e / 4) + 4 * (lane / 32) + e % 4;
-          float v = 0.f;
-          if (cls < C) v = (m < M) ? acc[(size_t)m * C + cls] : (m == 16 ? 1.f : 0.f);
-          uint16_t hi, lo;
-          host_split(v, hi, lo);
-          tab[((size_t)(ks * 2 + 0) * 64 + lane) * 8 + e] = hi;
-          tab[((size_t)(ks * 2 + 1) * 64 + lane) * 8 + e] = lo;
-        }
+    for (int lane = 0; lane < 64; ++lane)
+      for (int e = 0; e < 8; ++e) {
+        const int m = lane % 16, g = lane / 32, sl = (lane / 16) % 2;
+        const int cls = 32 * ct + 16 * sl + 8 * (e / 4) + 4 * g + e % 4;
+        const float v = (cls < C && m < M) ? acc[(size_t)m * C + cls] : 0.f;
+        uint16_t hi, lo;
+        host_split(v, hi, lo);
+        tab[((size_t)0 * 64 + lane) * 8 + e] = hi;
+        tab[((size_t)1 * 64 + lane) * 8 + e] = lo;
+      }
     float* bias = reinterpret_cast<float*>(blk + (size_t)(SB::kWUnits + SB::kTabUnits) * 16);
     for (int q = 0; q < 4; ++q)
       for (int g = 0; g < 2; ++g)
@@ -268,9 +273,10 @@ __device__ __forceinline__ float other_half(float v, int g) {
 // Softmax phase of one class tile (mostly vector ALU work): logits = acc * 2^-(ex+ew) + bias, online
 // softmax update, exponentials x table tile.
 template <int D, bool DUMP, bool SPLIT>
-__device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, float unscale, f32x16& eacc, float& m2,
-                                              int ct, int C, int g, int lane, bool valid, int64_t dump_row,
-                                              float* __restrict__ logits_out, float& best_z, int& best_c) {
+__device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, float unscale, f32x4& ea_lo, f32x4& ea_hi,
+                                              float& ssum, float& m2, int ct, int C, int g, int lane, bool valid,
+                                              int64_t dump_row, float* __restrict__ logits_out, float& best_z,
+                                              int& best_c) {
   using SB = SplitBlock<D>;
   // The other wavefront of this SIMD is, most of the time, streaming the MFMAs of its matrix phase and
   // always has the next one ready; without a higher priority the few MFMAs of this phase would wait
@@ -315,29 +321,69 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
   const float scale = __builtin_amdgcn_exp2f(m2 - m2n);
   m2 = m2n;
   const float shift = kExpShift - m2n;
+  // Exponentials x accuracy-table tile on 16x16x32 MFMAs (16 variants x 16 requests x 32 classes each):
+  // ea_lo of lane (row q = lane/16, j = lane%16) holds variants 4q..4q+3 of request j, ea_hi those of
+  // request 16 + j.  A lane's own request is lane%32, so in the odd rows ea_lo belongs to the neighbouring
+  // row's request and in the even rows ea_hi does: they take that row's rescaling factor.
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  {
+    const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(scale), __float_as_uint(scale), false, false);
+    const bool odd = (lane & 16) != 0;
+    const float nb = __uint_as_float(odd ? sw[0] : sw[1]);
+    const float sc_lo = odd ? nb : scale, sc_hi = odd ? scale : nb;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) eacc[v] *= scale;
-  // exponentials x table tile (accuracies and the row of ones), eight classes per lane at a time so that
-  // the first MFMAs are under way while the second half is still being exponentiated
-  const float4* tp = blk + SB::kWUnits + lane;
+    for (int v = 0; v < 4; ++v) {
+      ea_lo[v] *= sc_lo;
+      ea_hi[v] *= sc_hi;
+    }
+  }
+  // the softmax denominator of this lane's 16 classes is a plain sum (two chains)
+  float s0 = 0.f, s1 = 0.f;
+  f16x8 ph[2], pl[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
-    f16x8 ph, pl;
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
       const float p0 = __builtin_amdgcn_exp2f(fmaf(acc[8 * ks + e], kLog2e, shift));       // in (0, 2^14]
       const float p1 = __builtin_amdgcn_exp2f(fmaf(acc[8 * ks + e + 1], kLog2e, shift));
+      s0 += p0;
+      s1 += p1;
       f16x2 hi, lo;
       split_f16x2(p0, p1, hi, lo);
-      ph[e] = hi[0]; ph[e + 1] = hi[1];
-      pl[e] = lo[0]; pl[e + 1] = lo[1];
+      ph[ks][e] = hi[0]; ph[ks][e + 1] = hi[1];
+      pl[ks][e] = lo[0]; pl[ks][e + 1] = lo[1];
     }
-    const f16x8 th = as_f16x8(tp[(ks * 2 + 0) * 64]);
-    const f16x8 tl = as_f16x8(tp[(ks * 2 + 1) * 64]);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, ph, eacc, 0, 0, 0);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, ph, eacc, 0, 0, 0);
-    eacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, pl, eacc, 0, 0, 0);
   }
+  ssum = fmaf(ssum, scale, s0 + s1);
+  // Row swap: a lane holds classes slice 0 (ph[0]) and slice 1 (ph[1]) of its own request.  Exchanging
+  // slice 0 of the odd rows with slice 1 of the even rows leaves, in the first register set, requests
+  // 0..15 with K slices (g, slice) = (0,0), (0,1), (1,0), (1,1) in rows 0..3, and in the second set the
+  // same for requests 16..31: the B operands of the two MFMAs.
+  f16x8 bh_lo, bh_hi, bl_lo, bl_hi;
+  {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 h0 = __builtin_bit_cast(u32x4, ph[0]), h1 = __builtin_bit_cast(u32x4, ph[1]);
+    const u32x4 l0 = __builtin_bit_cast(u32x4, pl[0]), l1 = __builtin_bit_cast(u32x4, pl[1]);
+    u32x4 a_h, b_h, a_l, b_l;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x2 sh = __builtin_amdgcn_permlane16_swap(h0[i], h1[i], false, false);
+      const u32x2 sl = __builtin_amdgcn_permlane16_swap(l0[i], l1[i], false, false);
+      a_h[i] = sh[0]; b_h[i] = sh[1];
+      a_l[i] = sl[0]; b_l[i] = sl[1];
+    }
+    bh_lo = __builtin_bit_cast(f16x8, a_h); bh_hi = __builtin_bit_cast(f16x8, b_h);
+    bl_lo = __builtin_bit_cast(f16x8, a_l); bl_hi = __builtin_bit_cast(f16x8, b_l);
+  }
+  const float4* tp = blk + SB::kWUnits + lane;
+  const f16x8 th = as_f16x8(tp[0]);
+  const f16x8 tl = as_f16x8(tp[64]);
+  ea_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(th, bh_lo, ea_lo, 0, 0, 0);
+  ea_hi = __builtin_amdgcn_mfma_f32_16x16x32_f16(th, bh_hi, ea_hi, 0, 0, 0);
+  ea_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(tl, bh_lo, ea_lo, 0, 0, 0);
+  ea_hi = __builtin_amdgcn_mfma_f32_16x16x32_f16(tl, bh_hi, ea_hi, 0, 0, 0);
+  ea_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(th, bl_lo, ea_lo, 0, 0, 0);
+  ea_hi = __builtin_amdgcn_mfma_f32_16x16x32_f16(th, bl_hi, ea_hi, 0, 0, 0);
   __builtin_amdgcn_s_setprio(0);
 }
 
@@ -420,9 +466,8 @@ __device__ __forceinline__ void class_tiles_and_finish(
   float m2 = kNegBig;                                    // running maximum, in units of log2
   float best_z = kNegBig;                                // largest logit of this lane's classes and its class
   int best_c = 0x7fffffff;
-  f32x16 eacc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) eacc[v] = 0.f;
+  f32x4 ea_lo = {0.f, 0.f, 0.f, 0.f}, ea_hi = {0.f, 0.f, 0.f, 0.f};   // EA numerators (layout: softmax_phase)
+  float ssum = 0.f;                                      // softmax denominator of this lane's classes
   const int64_t dump_row = (int64_t)id * tb.Cmax;
 
   // The class tiles are software-pipelined inside every wavefront: an iteration holds the matrix phase
@@ -456,11 +501,11 @@ __device__ __forceinline__ void class_tiles_and_finish(
       if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
       stage_park<D, 0>(FILL, stg, tid);   /* (past the last block: a copy nobody reads) */                     \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
-      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row,            \
-                                    logits_out, best_z, best_c);                                               \
+      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, ea_lo, ea_hi, ssum, m2, (T), C, g, lane, valid,        \
+                                    dump_row, logits_out, best_z, best_c);                                     \
     } else {                                                                                                   \
-      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, eacc, m2, (T), C, g, lane, valid, dump_row,            \
-                                    logits_out, best_z, best_c);                                               \
+      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, ea_lo, ea_hi, ssum, m2, (T), C, g, lane, valid,        \
+                                    dump_row, logits_out, best_z, best_c);                                     \
       stage_park<D, 0>(FILL, stg, tid);                                                                        \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
       if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
@@ -476,6 +521,22 @@ __device__ __forceinline__ void class_tiles_and_finish(
   }
 #undef SP_TILE
   if (DUMP) return;
+  // Back to one request per lane pair for the epilogue: lane (r, g) takes variants 4g..4g+3 from row g and
+  // 8+4g..8+4g+3 from row 2+g, column r%16, out of ea_lo (r < 16) or ea_hi; entry 8 is the denominator.
+  f32x16 eacc;
+  {
+    const int src_a = 16 * g + (r & 15), src_b = 16 * (2 + g) + (r & 15);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float a_lo = __shfl(ea_lo[v], src_a), a_hi = __shfl(ea_hi[v], src_a);
+      const float b_lo = __shfl(ea_lo[v], src_b), b_hi = __shfl(ea_hi[v], src_b);
+      eacc[v] = r < 16 ? a_lo : a_hi;
+      eacc[4 + v] = r < 16 ? b_lo : b_hi;
+    }
+    eacc[8] = ssum + other_half(ssum, g);
+#pragma unroll
+    for (int v = 9; v < 16; ++v) eacc[v] = 0.f;
+  }
   score_epilogue<SPLIT>(tb, w, eacc, m2, best_z, best_c, a, M, pos, id, valid, r, g, Dl, wt, sortkey);
 }
 
