@@ -9,10 +9,12 @@
 //
 // The unit of work is one wavefront walking `unit` consecutive elements of one
 // segment 64 at a time, in order; units never straddle segments.  A pass is
-// four kernels: per-unit digit histograms, a scan down every (segment, digit)
-// column, a scan over each segment's 256 column totals, and the scatter, in which every wavefront ranks its 64
-// elements per digit with ballots (equal digits keep their order) and bumps a
-// wavefront-private running offset table in LDS.  No inter-workgroup waiting.
+// three kernels: per-unit digit histograms, a scan down every (segment, digit)
+// column, and the scatter, in which every wavefront first redoes the small scan
+// over its segment's 256 column totals, then ranks its elements 64 at a time per
+// digit with ballots (equal digits keep their order) and bumps a
+// wavefront-private running offset table in LDS.  A unit's keys and values are
+// all requested before the first is used.  No inter-workgroup waiting.
 #pragma once
 #include "sp_common.h"
 #include "sp_wave.h"
