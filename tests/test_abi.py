@@ -98,3 +98,12 @@ def test_null_context_is_rejected(lib):
     assert lib.sp_schedule(None, 0, None, None, None, None, None, None, 0, None) == binding.SP_EINVAL
     assert lib.sp_max_models(None) == 0
     lib.sp_destroy(None)
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(tmp_path):
+    # the product path has no CPU substitute: without the built library, loading raises
+    from paper_2505_06641_amd import binding
+    with pytest.raises(RuntimeError, match="is missing"):
+        binding.load_library(str(tmp_path / "libsneakpeek_hip.so"))
+    src = open(binding.__file__).read()
+    assert "oracle" not in src.replace("the binding and the oracle", "")
