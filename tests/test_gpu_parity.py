@@ -650,3 +650,24 @@ def test_matrix_core_rate_diagnostic(gpu):
     with pytest.raises(binding.SneakPeekError) as e:
         binding.sp_debug_mfma_rate(True, iters=0)
     assert e.value.status == binding.SP_EINVAL
+
+
+def test_a_caller_stream_is_honoured(gpu):
+    """Everything a window launches goes to the stream the caller names: the same window on a stream of the
+    caller's own (default priority), behind other work queued on that stream, gives bit-identical results."""
+    torch, binding = gpu
+    w = wl.tiny(seed=7700, n=3000, classes=(40, 7, 90), models=(5, 16, 3), max_batch=12, feat_dim=48, deadline=(4.0, 90.0))
+    ref = run_window(gpu, w, 0, want_cube=True)
+    side = torch.cuda.Stream()
+    noise = torch.randn(2048, 2048, device="cuda:0")
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            noise = noise @ noise * 1e-3               # unrelated work ahead of the window on the same stream
+        got = run_window(gpu, w, 0, want_cube=True)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert got["log"] == ref["log"] and got["summary"] == ref["summary"]
+    for k in ("ea", "key", "order", "seg", "cube", "model", "round_of", "order_of", "util"):
+        assert np.array_equal(got[k], ref[k], equal_nan=True), k
+    ref["close"]()
+    got["close"]()
