@@ -671,3 +671,37 @@ def test_a_caller_stream_is_honoured(gpu):
         assert np.array_equal(got[k], ref[k], equal_nan=True), k
     ref["close"]()
     got["close"]()
+
+
+def test_two_contexts_interleaved_are_independent(gpu):
+    """Separate contexts share nothing: windows of two contexts scheduled in alternating chunks end exactly
+    as when each runs alone."""
+    torch, binding = gpu
+    wa = wl.tiny(seed=7800, n=2500, classes=(30, 8), models=(4, 9), max_batch=10, feat_dim=40, deadline=(4.0, 120.0))
+    wb = wl.tiny(seed=7801, n=1800, classes=(5, 60, 12), models=(16, 2, 7), max_batch=6, feat_dim=24, hidden_dim=12,
+                 feat_dtype=wl.BF16, deadline=(3.0, 80.0))
+    alone = [run_window(gpu, w, 0) for w in (wa, wb)]
+    ctxs = [binding.Context(w.profile, w.requests.n) for w in (wa, wb)]
+    devs = [binding.to_device(w.requests) for w in (wa, wb)]
+    outs = []
+    for ctx, (x, app, D, wt), w in zip(ctxs, devs, (wa, wb)):
+        ctx.sp_score(x, app, D, wt)
+        n = w.requests.n
+        outs.append([torch.full((n,), 99, dtype=torch.int32, device="cuda:0") for _ in range(3)] +
+                    [torch.full((n,), -7.0, device="cuda:0")])
+    done = [False, False]
+    logs = [[], []]
+    summ = [None, None]
+    while not all(done):
+        for i, ctx in enumerate(ctxs):
+            if done[i]:
+                continue
+            rc, sm, _ = ctx.sp_schedule(3, *outs[i], log_capacity=0)
+            summ[i] = sm
+            done[i] = rc == binding.SP_DONE
+    for i in range(2):
+        assert summ[i] == alone[i]["summary"]
+        for t, k in zip(outs[i], ("model", "round_of", "order_of", "util")):
+            assert np.array_equal(t.cpu().numpy(), alone[i][k]), (i, k)
+        ctxs[i].close()
+        alone[i]["close"]()
