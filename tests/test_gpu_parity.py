@@ -705,3 +705,16 @@ def test_two_contexts_interleaved_are_independent(gpu):
             assert np.array_equal(t.cpu().numpy(), alone[i][k]), (i, k)
         ctxs[i].close()
         alone[i]["close"]()
+
+
+@pytest.mark.parametrize("name", ["sneakpeek", "alg1"])
+def test_many_rounds_across_several_launches(gpu, name):
+    """Several hundred rounds in one sp_schedule call: the one-launch kernel is launched again every 64
+    rounds and has to pick up clock, resident variant (swap-in costs), head pointers and generation
+    numbers where the previous launch left them."""
+    w = wl.tiny(seed=7900, n=700, classes=(6, 20, 3), models=(3, 5, 2), max_batch=3, feat_dim=16, penalty=wl.PEN_LINEAR,
+                deadline=(200.0, 2500.0), alpha=(1.0, 4.0), beta=(0.2, 1.0), fractions=(0.5, 0.3, 0.2))
+    wl.attach_swap_costs(w.profile, seed=7901, lo=0.5, hi=5.0)
+    got, stats = full_parity(gpu, w, max_rounds=0, policy=wl.named_policy(name), want_cube=True)
+    assert stats["rounds"] > 150 and got["summary"]["done"] == 1
+    assert got["summary"]["n_scheduled"] + got["summary"]["n_dropped"] == 700 and got["summary"]["total_violation_ms"] > 0
