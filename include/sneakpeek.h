@@ -285,6 +285,15 @@ int32_t sp_max_classes(const sp_ctx* ctx);
 int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 
 /*
+ * Test hook, not on the hot path.  The one-launch rounds kernel (Alg. 1's rounds, Sec. 5.1.1) tags the words
+ * its workgroups exchange with a round generation number that grows by one per round over the life of the
+ * context and starts over, with the exchange buffers cleared, before it would exceed 2^23 - 1 (after some
+ * eight million rounds).  This sets the number of generations used so far, so that a test can place a window
+ * across that point.  Call it between windows only.  SP_EINVAL: ctx NULL or generation >= 2^23 - 1.
+ */
+sp_status sp_debug_set_generation(sp_ctx* ctx, uint32_t generation);
+
+/*
  * Diagnostic, not on the hot path: the rate at which the device's matrix cores run the half-precision
  * instruction the scoring kernel is built on (posterior of Def. 4.1.2 and the contraction of Sec. 4.1
  * eq. (9)) when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.

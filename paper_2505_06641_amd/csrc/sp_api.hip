@@ -1040,6 +1040,12 @@ int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
 int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist && !c->tb.pol_split) ? 1 : 0; }
 
+sp_status sp_debug_set_generation(sp_ctx* c, uint32_t generation) {
+  if (!c || generation >= kGenMask) return SP_EINVAL;
+  c->gen_base = generation;
+  return SP_OK;
+}
+
 sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, void* stream, double* tflops_out,
                              double* clock_ghz_out) {
   if (iters < 1 || iters > (1 << 20) || !tflops_out) return SP_EINVAL;

@@ -718,3 +718,28 @@ def test_many_rounds_across_several_launches(gpu, name):
     got, stats = full_parity(gpu, w, max_rounds=0, policy=wl.named_policy(name), want_cube=True)
     assert stats["rounds"] > 150 and got["summary"]["done"] == 1
     assert got["summary"]["n_scheduled"] + got["summary"]["n_dropped"] == 700 and got["summary"]["total_violation_ms"] > 0
+
+
+def test_round_generations_start_over_cleanly(gpu):
+    """The exchange words of the one-launch rounds kernel carry generation numbers that start over after
+    2^23 - 1 rounds in the life of a context: a window placed across that point is scheduled exactly as
+    one that is not."""
+    torch, binding = gpu
+    w = wl.tiny(seed=7900, n=700, classes=(6, 20, 3), models=(3, 5, 2), max_batch=3, feat_dim=16, penalty=wl.PEN_LINEAR,
+                deadline=(200.0, 2500.0), alpha=(1.0, 4.0), beta=(0.2, 1.0), fractions=(0.5, 0.3, 0.2))
+    ref = run_window(gpu, w, 0)
+    assert ref["summary"]["n_rounds"] > 150
+    ctx = binding.Context(w.profile, 700)
+    if not ctx.rounds_in_one_launch:
+        pytest.skip("this device does not hold the one-launch rounds kernel")
+    ctx.sp_debug_set_generation((1 << 23) - 1 - 100)         # the second launch of the window reaches the limit
+    got = run_window(gpu, w, 0, ctx=ctx)
+    assert got["log"] == ref["log"] and got["summary"] == ref["summary"]
+    for k in ("model", "round_of", "order_of", "util"):
+        assert np.array_equal(got[k], ref[k]), k
+    got2 = run_window(gpu, w, 0, ctx=ctx)                     # and the context goes on normally afterwards
+    assert got2["log"] == ref["log"] and got2["summary"] == ref["summary"]
+    with pytest.raises(binding.SneakPeekError):
+        ctx.sp_debug_set_generation(1 << 23)
+    ctx.close()
+    ref["close"]()
