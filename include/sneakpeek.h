@@ -294,6 +294,16 @@ int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 sp_status sp_debug_set_generation(sp_ctx* ctx, uint32_t generation);
 
 /*
+ * Test hook, not on the hot path.  The workgroups of the one-launch rounds kernel wait for each other with
+ * bounded polling; a wait that runs out (the device is shared with other long-running work and the grid is
+ * not resident as a whole) makes every workgroup leave, sp_schedule return SP_EDEVICE, and the context use
+ * two kernels per round from then on (the window has to be scored again).  polls > 0 shortens the bound so
+ * that a test can take that path with every kernel still ending normally; 0 restores the default (2^20).
+ * SP_EINVAL: ctx NULL or polls < 0.
+ */
+sp_status sp_debug_set_spin_limit(sp_ctx* ctx, int32_t polls);
+
+/*
  * Diagnostic, not on the hot path: the rate at which the device's matrix cores run the half-precision
  * instruction the scoring kernel is built on (posterior of Def. 4.1.2 and the contraction of Sec. 4.1
  * eq. (9)) when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.

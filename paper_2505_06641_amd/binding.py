@@ -21,7 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_set_generation", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
+           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -113,6 +113,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_rounds_in_one_launch.restype = C.c_int32
     lib.sp_debug_set_generation.argtypes = [vp, C.c_uint32]
     lib.sp_debug_set_generation.restype = C.c_int
+    lib.sp_debug_set_spin_limit.argtypes = [vp, C.c_int32]
+    lib.sp_debug_set_spin_limit.restype = C.c_int
     lib.sp_debug_mfma_rate.argtypes = [C.c_int, C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.sp_debug_mfma_rate.restype = C.c_int
     lib.sp_set_timing.argtypes = [vp, C.c_int32]
@@ -300,6 +302,9 @@ class Context:
         n = C.c_int32(0)
         self._check(self.lib.sp_get_round_times(self.h, buf, capacity, C.byref(n)), "sp_get_round_times")
         return [buf[i] for i in range(n.value)]
+
+    def sp_debug_set_spin_limit(self, polls):
+        return self._check(self.lib.sp_debug_set_spin_limit(self.h, int(polls)), "sp_debug_set_spin_limit")
 
     def sp_debug_set_generation(self, generation):
         return self._check(self.lib.sp_debug_set_generation(self.h, int(generation)), "sp_debug_set_generation")

@@ -55,6 +55,7 @@ struct sp_ctx {
   bool persist = false;
   Persist ps{};
   uint32_t gen_base = 0;             // slot generations handed out so far
+  int32_t spin_limit = kSpinLimit;   // polls before a wait between resident workgroups is given up
   long long* h_ticks = nullptr;      // pinned mirror of ps.ticks
   double tick_ms = 0.0;              // milliseconds per timestamp tick
   std::vector<float> round_ms;       // per-round latencies of the last timed sp_schedule on that path
@@ -459,6 +460,7 @@ sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
     c->gen_base = 0;
   }
   ps.n_rounds = n_rounds;
+  ps.spin_limit = c->spin_limit;
   ps.gen_base = c->gen_base;
   c->gen_base += (uint32_t)n_rounds;
   hipLaunchKernelGGL(k_rounds_persistent, dim3(ps.n_pairs + 2), dim3(kRoundThreads), 0, s, c->tb, c->w, ps);
@@ -1039,6 +1041,12 @@ sp_status sp_set_swap_cost(sp_ctx* c, int32_t app, const float* swap_ms_host) {
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
 int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist && !c->tb.pol_split) ? 1 : 0; }
+
+sp_status sp_debug_set_spin_limit(sp_ctx* c, int32_t polls) {
+  if (!c || polls < 0) return SP_EINVAL;
+  c->spin_limit = polls == 0 ? kSpinLimit : polls;
+  return SP_OK;
+}
 
 sp_status sp_debug_set_generation(sp_ctx* c, uint32_t generation) {
   if (!c || generation >= kGenMask) return SP_EINVAL;

@@ -45,6 +45,7 @@ struct Persist {
   const int32_t* pair_model;    // [n_pairs] variant of each pair
   int32_t n_pairs;
   int32_t n_rounds;             // rounds this launch may run (<= kPersistRounds)
+  int32_t spin_limit;           // polls before a wait between workgroups is given up (kSpinLimit unless a test shortens it)
   uint32_t gen_base;            // generations used by earlier launches
   unsigned long long* slots;    // [2 (parity), n_pairs, 4 (word)]
   unsigned long long* decision; // [2 (parity), 4 (word)]: latency bits << 32 | gen; (candidate id + 1, 0 = none)
@@ -82,7 +83,7 @@ __device__ void persist_commit_loop(const Tables& tb, const Window& w, const Per
     const uint32_t gen = ps.gen_base + (uint32_t)rl + 1u;
     if (tid == 0) {
       unsigned long long v = 0ull;
-      for (int i = 0; i < kSpinLimit; ++i) {
+      for (int i = 0; i < ps.spin_limit; ++i) {
         v = ld_dev(ps.dec + rl);
         if (v != 0ull) break;
         __builtin_amdgcn_s_sleep(4);
@@ -109,7 +110,7 @@ __device__ void persist_commit_loop(const Tables& tb, const Window& w, const Per
     commit_members(tb, w, a, m, b, r, next_order, E,
                    [&](int j) {
                      unsigned long long e = 0ull;
-                     for (int i = 0; i < kSpinLimit; ++i) {
+                     for (int i = 0; i < ps.spin_limit; ++i) {
                        e = ld_dev(row + j);
                        if ((uint32_t)(e >> 32) == gen) break;
                        __builtin_amdgcn_s_sleep(4);
@@ -164,7 +165,7 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
       const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + i) * 4;
       unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull, v3 = 0ull;
       bool ok = false;
-      for (int k = 0; k < kSpinLimit; ++k) {
+      for (int k = 0; k < ps.spin_limit; ++k) {
         v0 = ld_dev(slot);
         v1 = ld_dev(slot + 1);
         v2 = ld_dev(slot + 2);
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
       const unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 4;
       unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull;
       bool ok = false;
-      for (int k = 0; k < kSpinLimit; ++k) {
+      for (int k = 0; k < ps.spin_limit; ++k) {
         v0 = ld_dev(d);
         v1 = ld_dev(d + 1);
         v2 = ld_dev(d + 2);

@@ -743,3 +743,32 @@ def test_round_generations_start_over_cleanly(gpu):
         ctx.sp_debug_set_generation(1 << 23)
     ctx.close()
     ref["close"]()
+
+
+def test_a_wait_that_runs_out_fails_the_call_and_the_context_carries_on_with_two_kernels(gpu):
+    """The bounded waits of the one-launch rounds kernel, forced to run out from the host (a poll limit of
+    one; every kernel still ends normally): sp_schedule reports SP_EDEVICE, the window has to be scored
+    again, and from then on the context schedules with two kernels per round, with the same decisions."""
+    torch, binding = gpu
+    w = wl.tiny(seed=7950, n=2000, classes=(9, 30), models=(4, 7), max_batch=8, feat_dim=20, deadline=(4.0, 90.0))
+    ref = run_window(gpu, w, 0)
+    ctx = binding.Context(w.profile, 2000)
+    if not ctx.rounds_in_one_launch:
+        pytest.skip("this device does not hold the one-launch rounds kernel")
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_debug_set_spin_limit(1)
+    ctx.sp_score(x, app, D, wt)
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_schedule(0, log_capacity=16)
+    assert e.value.status == binding.SP_EDEVICE
+    assert not ctx.lib.sp_rounds_in_one_launch(ctx.h)
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_schedule(0, log_capacity=16)                   # the window's state is not to be trusted any more
+    assert e.value.status == binding.SP_ESTATE
+    ctx.sp_debug_set_spin_limit(0)
+    got = run_window(gpu, w, 0, ctx=ctx)                      # scored again, two kernels per round
+    assert got["log"] == ref["log"] and got["summary"] == ref["summary"]
+    for k in ("model", "round_of", "order_of", "util"):
+        assert np.array_equal(got[k], ref[k]), k
+    ctx.close()
+    ref["close"]()
