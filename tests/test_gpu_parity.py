@@ -490,6 +490,18 @@ def test_more_than_255_applications_two_pass_grouping(gpu):
     assert got["summary"]["done"] == 1 and stats["rounds"] >= 20
 
 
+def test_more_applications_than_the_segment_table_holds(gpu):
+    """Beyond 1024 applications k_segments places tiles and units without its LDS tables, the scan's
+    digit totals are one row per application, and the rounds run over more than a thousand groups."""
+    A = 1100
+    rng = np.random.default_rng(11)
+    frac = rng.dirichlet(np.full(A, 0.5))
+    w = wl.tiny(seed=103, n=6000, classes=tuple(2 + (a % 4) for a in range(A)), models=tuple(1 + (a % 2) for a in range(A)),
+                max_batch=4, feat_dim=6, deadline=(5.0, 60.0), fractions=tuple(frac / frac.sum()))
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=False)
+    assert stats["rounds"] >= 20 and got["summary"]["done"] == 1
+
+
 def test_largest_batch_variant_and_class_counts(gpu):
     """B = 256 and M = 16 (the library's limits) with C well beyond one class tile, on the matrix-core kernel."""
     w = wl.tiny(seed=103, n=900, classes=(1500, 700), models=(16, 16), max_batch=256, feat_dim=64, deadline=(20.0, 900.0),
