@@ -59,6 +59,7 @@ struct sp_ctx {
   long long* h_ticks = nullptr;      // pinned mirror of ps.ticks
   double tick_ms = 0.0;              // milliseconds per timestamp tick
   std::vector<float> round_ms;       // per-round latencies of the last timed sp_schedule on that path
+  int32_t rounds_in_call = 0;        // rounds the last sp_schedule call committed
   // host copies needed to fold a prior into the expected accuracies (sp_set_prior)
   std::vector<float> h_acc;
   std::vector<int32_t> h_acc_off, h_ncls, h_nmod;
@@ -833,6 +834,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   }
   if (!fetched && (st = fetch_state(c, s)) != SP_OK) return st;
   c->timed_rounds = tm && fetched;
+  c->rounds_in_call = c->rounds_done - start;
   bool pending = false;
   if (c->n > 0 && !outputs_copied && (model_out_dev || round_out_dev || order_out_dev || util_out_dev)) {
     hipLaunchKernelGGL(k_copy_outputs, dim3((c->n + 255) / 256), dim3(256), 0, s, c->n, c->w, model_out_dev,
@@ -927,7 +929,7 @@ sp_status sp_get_timing(sp_ctx* c, sp_timing* out) {
   if (c->timed_rounds) {
     SP_HIP(c, hipEventSynchronize(c->ev[5]));
     SP_HIP(c, hipEventElapsedTime(&t.rounds_ms, c->ev[4], c->ev[5]));
-    t.n_rounds_timed = c->round_ms.empty() ? c->n_round_ev : (int32_t)c->round_ms.size();
+    t.n_rounds_timed = c->round_ms.empty() ? std::min(c->n_round_ev, c->rounds_in_call) : (int32_t)c->round_ms.size();
   }
   *out = t;
   return SP_OK;
@@ -944,7 +946,8 @@ sp_status sp_get_round_times(sp_ctx* c, float* ms_out, int32_t capacity, int32_t
     *n_out = n;
     return SP_OK;
   }
-  const int n = std::min(capacity, c->n_round_ev);
+  // an event follows every round that was launched; only those that committed a batch count
+  const int n = std::min(capacity, std::min(c->n_round_ev, c->rounds_in_call));
   for (int i = 0; i < n; ++i) {
     SP_HIP(c, hipEventSynchronize(c->round_ev[i]));
     SP_HIP(c, hipEventElapsedTime(&ms_out[i], i == 0 ? c->ev[4] : c->round_ev[i - 1], c->round_ev[i]));

@@ -784,3 +784,36 @@ def test_a_wait_that_runs_out_fails_the_call_and_the_context_carries_on_with_two
         assert np.array_equal(got[k], ref[k]), k
     ctx.close()
     ref["close"]()
+
+
+@pytest.mark.parametrize("path", ["one launch", "two kernels"])
+def test_timing_aid_changes_nothing_and_reports_sane_times(gpu, path):
+    """sp_set_timing: the same schedule with stage and per-round timing on, on both rounds paths; the
+    times are positive, one per round, and add up to no more than the whole."""
+    torch, binding = gpu
+    if path == "one launch":
+        w = wl.tiny(seed=7960, n=2500, classes=(9, 30), models=(4, 7), max_batch=8, feat_dim=20, deadline=(4.0, 90.0))
+    else:
+        A = 90                                               # too many (application, variant) pairs to stay resident
+        w = wl.tiny(seed=7961, n=4000, classes=tuple(2 + (a % 5) for a in range(A)), models=tuple(9 + (a % 4) for a in range(A)),
+                    max_batch=7, feat_dim=12, deadline=(5.0, 90.0))
+    ref = run_window(gpu, w, 0)
+    ctx = binding.Context(w.profile, w.requests.n)
+    if (path == "one launch") != ctx.rounds_in_one_launch:
+        pytest.skip("this device runs the rounds of this profile the other way")
+    with pytest.raises(binding.SneakPeekError) as e:
+        ctx.sp_get_timing()
+    assert e.value.status == binding.SP_ESTATE
+    ctx.sp_set_timing(2)
+    got = run_window(gpu, w, 0, ctx=ctx)
+    assert got["log"] == ref["log"] and got["summary"] == ref["summary"]
+    tm = ctx.sp_get_timing()
+    per_round = ctx.sp_get_round_times()
+    n_rounds = ref["summary"]["n_rounds"]
+    assert tm["n_rounds_timed"] == len(per_round) == n_rounds
+    assert all(0.0 < t < 5.0 for t in per_round)             # milliseconds
+    assert 0.0 < tm["score_kernel_ms"] < 50.0 and 0.0 < tm["group_ms"] < 50.0 and 0.0 < tm["order_ms"] < 50.0
+    assert sum(per_round) <= tm["rounds_ms"] * 1.05 + 0.05
+    ctx.sp_set_timing(0)
+    ctx.close()
+    ref["close"]()
