@@ -817,3 +817,28 @@ def test_timing_aid_changes_nothing_and_reports_sane_times(gpu, path):
     ctx.sp_set_timing(0)
     ctx.close()
     ref["close"]()
+
+
+def test_optional_outputs_short_log_and_calls_after_the_end(gpu):
+    """sp_schedule with only some outputs, a log shorter than the schedule, and further calls once nothing
+    is live: the same schedule, the log's first entries, SP_DONE with the same summary."""
+    torch, binding = gpu
+    w = wl.tiny(seed=7970, n=1500, classes=(9, 30), models=(4, 7), max_batch=8, feat_dim=20, deadline=(4.0, 90.0))
+    ref = run_window(gpu, w, 0)
+    assert ref["summary"]["n_rounds"] > 8
+    ctx = binding.Context(w.profile, 1500)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_score(x, app, D, wt)                              # no EA / key outputs asked for
+    util = torch.full((1500,), -7.0, device="cuda:0")
+    rc, summ, log = ctx.sp_schedule(0, util_out=util, log_capacity=5)
+    assert rc == binding.SP_DONE and summ == ref["summary"]
+    assert log == ref["log"][:5]
+    assert np.array_equal(util.cpu().numpy(), ref["util"])
+    model = torch.full((1500,), 99, dtype=torch.int32, device="cuda:0")
+    rc, summ2, log2 = ctx.sp_schedule(0, model_out=model, log_capacity=1500)     # nothing left to do
+    assert rc == binding.SP_DONE and summ2 == ref["summary"] and log2 == ref["log"]
+    assert np.array_equal(model.cpu().numpy(), ref["model"])
+    rc, dec = ctx.sp_greedy_round()
+    assert rc == binding.SP_DONE
+    ctx.close()
+    ref["close"]()
