@@ -164,6 +164,20 @@ sp_status sp_score(sp_ctx* ctx, int32_t n, const void* x_dev, const int32_t* app
  * live, SP_ESTATE before the first sp_score.                                   */
 sp_status sp_greedy_round(sp_ctx* ctx, void* stream, sp_decision* out_host, int32_t* req_ids_out_dev);
 
+/* sp_greedy_round for callers that must not allocate device memory and want the library to touch none
+ * that was allocated for it either: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same decision, same status codes as sp_greedy_round; the buffers the
+ * two round kernels exchange through (one candidate word and one group priority per (group, variant), the
+ * window positions and window size per group) live in a static device array of 1 MiB that every GPU the
+ * library runs on holds until the process ends, instead of in the context.  The call allocates and frees
+ * nothing.  SP_ECAPACITY (nothing launched) when
+ *   G * Mmax * 12 + G * B * 4 + G * 4 bytes, each term rounded up to 256,
+ * exceed 1 MiB, G being the number of groups the context can hold (A, or the (application, subgroup)
+ * slots once group splitting has been switched on).  All contexts on one GPU share that array and it
+ * keeps the last call's contents (every word a round reads is written by that round first, so nothing has
+ * to be cleared): calls that overlap on one GPU, from different contexts or streams, race.               */
+sp_status sp_greedy_round_static(sp_ctx* ctx, void* stream, sp_decision* out_host, int32_t* req_ids_out_dev);
+
 /* Greedy rounds until nothing is live, or until max_rounds more rounds have
  * been committed (max_rounds <= 0: no limit).  Rounds run back to back on the
  * device; the call waits for the stream before returning.

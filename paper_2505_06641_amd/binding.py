@@ -19,7 +19,7 @@ SP_OK, SP_DONE = 0, 1
 SP_EINVAL, SP_ENOMEM, SP_EDEVICE, SP_ESTATE, SP_ECAPACITY = -1, -2, -3, -4, -5
 SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
-EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_schedule", "sp_debug_dump",
+EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_greedy_round_static", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
            "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
@@ -90,6 +90,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_score.restype = C.c_int
     lib.sp_greedy_round.argtypes = [vp, vp, C.POINTER(sp_decision), i32p]
     lib.sp_greedy_round.restype = C.c_int
+    lib.sp_greedy_round_static.argtypes = [vp, vp, C.POINTER(sp_decision), i32p]
+    lib.sp_greedy_round_static.restype = C.c_int
     lib.sp_schedule.argtypes = [vp, C.c_int32, vp, i32p, i32p, i32p, vp, C.POINTER(sp_decision), C.c_int32,
                                 C.POINTER(sp_summary)]
     lib.sp_schedule.restype = C.c_int
@@ -251,6 +253,13 @@ class Context:
         d = sp_decision()
         rc = self.lib.sp_greedy_round(self.h, _stream_ptr(stream), C.byref(d), _dptr(req_ids_out))
         self._check(rc, "sp_greedy_round", ok=(SP_OK, SP_DONE))
+        return rc, (d.as_dict() if rc == SP_OK else None)
+
+    def sp_greedy_round_static(self, req_ids_out=None, stream=None):
+        """sp_greedy_round on the library's static scratch array; returns (status, decision dict or None)."""
+        d = sp_decision()
+        rc = self.lib.sp_greedy_round_static(self.h, _stream_ptr(stream), C.byref(d), _dptr(req_ids_out))
+        self._check(rc, "sp_greedy_round_static", ok=(SP_OK, SP_DONE))
         return rc, (d.as_dict() if rc == SP_OK else None)
 
     def sp_schedule(self, max_rounds=0, model_out=None, round_out=None, order_out=None, util_out=None,

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -72,6 +73,7 @@ struct sp_ctx {
   int32_t* h_grp_n = nullptr;        // pinned: number of groups of the scored window
   hipEvent_t ev_groups = nullptr;    // recorded after the copy into h_grp_n
   int sub_passes = 0;                // 8-bit radix passes over the subgroup codes
+  unsigned char* static_scratch = nullptr;   // this device's copy of the static scratch array (sp_greedy_round_static)
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
@@ -83,6 +85,17 @@ struct sp_ctx {
 };
 
 constexpr int kMaxRoundEvents = 4096;
+
+// Device memory for sp_greedy_round_static: the per-round exchange buffers of the two round kernels
+// (candidate words, group priorities, window positions and sizes), for callers that must not allocate.
+// One copy per GPU for the life of the process; `scratch` is only a host-side handle here: its device
+// address on each GPU comes from hipGetSymbolAddress (static_scratch_for) and that address is what
+// kernels and memory calls get.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kStaticMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kStaticMaxDevices];   // device address of `scratch` on each GPU seen so far
+static std::mutex g_scratch_mu;
 
 namespace {
 
@@ -534,6 +547,22 @@ void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, con
 
 int score_tile(const sp_ctx* c) { return (c->mfma_D > 0 || c->mlp_bf16) ? kMfTile : kScoreTile; }
 
+// Address of the static scratch array on `device` (which must be current), looked up once per device.
+sp_status static_scratch_for(sp_ctx* c, int device, unsigned char** out) {
+  if (device < 0 || device >= kStaticMaxDevices) return SP_ECAPACITY;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    SP_HIP(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SP_EDEVICE;
+    g_scratch_ptr[device] = (unsigned char*)p;
+  }
+  *out = g_scratch_ptr[device];
+  return SP_OK;
+}
+
+constexpr size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
 void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
                   uint32_t* sortkey, float* logits) {
   if (c->mlp_bf16) {
@@ -601,10 +630,10 @@ int group_count(sp_ctx* c) {
   return std::max(1, (int)*c->h_grp_n);
 }
 
-void launch_round(sp_ctx* c, hipStream_t s, int32_t* ids_out, float* cube) {
-  hipLaunchKernelGGL(k_round_score, dim3(group_count(c) * c->Mmax), dim3(kRoundThreads), 0, s, c->tb, c->w, cube);
+void launch_round(sp_ctx* c, const Window& w, hipStream_t s, int32_t* ids_out, float* cube) {
+  hipLaunchKernelGGL(k_round_score, dim3(group_count(c) * c->Mmax), dim3(kRoundThreads), 0, s, c->tb, w, cube);
   if (cube == nullptr)
-    hipLaunchKernelGGL(k_round_commit, dim3(1), dim3(kRoundThreads), 0, s, c->tb, c->w, ids_out);
+    hipLaunchKernelGGL(k_round_commit, dim3(1), dim3(kRoundThreads), 0, s, c->tb, w, ids_out);
 }
 
 // Brings the window state to the host.  mirrored: the last kernel on the stream was k_round_commit, which
@@ -648,6 +677,7 @@ sp_status sp_create(const sp_profile* profile, int device_id, sp_ctx** out) {
     return SP_EDEVICE;
   }
   s = build_ctx(c, profile);
+  if (s == SP_OK) s = static_scratch_for(c, device_id, &c->static_scratch);
   if (s != SP_OK) {
     sp_destroy(c);
     return s;
@@ -777,7 +807,39 @@ sp_status sp_greedy_round(sp_ctx* c, void* stream, sp_decision* out_host, int32_
   if (!g.ok) return SP_EDEVICE;
   hipStream_t s = (hipStream_t)stream;
   const int32_t before = c->rounds_done;
-  launch_round(c, s, req_ids_out_dev, nullptr);
+  launch_round(c, c->w, s, req_ids_out_dev, nullptr);
+  sp_status st = fetch_state(c, s, true);
+  if (st != SP_OK) return st;
+  if (c->rounds_done == before) return SP_DONE;
+  if (out_host) std::memcpy(out_host, &c->h_state->last, sizeof(sp_decision));
+  return SP_OK;
+}
+
+sp_status sp_greedy_round_static(sp_ctx* c, void* stream, sp_decision* out_host, int32_t* req_ids_out_dev) {
+  if (!c) return SP_EINVAL;
+  if (!c->scored) return SP_ESTATE;
+  // the round kernels' exchange buffers, carved out of the static array instead of the context's own
+  const size_t G = (size_t)c->w.gcap, GM = G * (size_t)c->Mmax;
+  const size_t o_cand = 0, o_prio = o_cand + align256(GM * sizeof(unsigned long long));
+  const size_t o_pos = o_prio + align256(GM * sizeof(float));
+  const size_t o_n = o_pos + align256(G * (size_t)c->B * sizeof(int32_t));
+  const size_t need = o_n + align256(G * sizeof(int32_t));
+  if (need > kStaticScratchBytes) {
+    c->hip_err = "sp_greedy_round_static: groups x variants x batch sizes exceed the static scratch array";
+    return SP_ECAPACITY;
+  }
+  if (!c->static_scratch) return SP_EDEVICE;
+  DeviceGuard g(c->device);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  Window w = c->w;
+  unsigned char* base = c->static_scratch;
+  w.cand = reinterpret_cast<unsigned long long*>(base + o_cand);
+  w.cand_prio = reinterpret_cast<float*>(base + o_prio);
+  w.win_pos = reinterpret_cast<int32_t*>(base + o_pos);
+  w.win_n = reinterpret_cast<int32_t*>(base + o_n);
+  const int32_t before = c->rounds_done;
+  launch_round(c, w, s, req_ids_out_dev, nullptr);
   sp_status st = fetch_state(c, s, true);
   if (st != SP_OK) return st;
   if (c->rounds_done == before) return SP_DONE;
@@ -813,7 +875,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
         SP_HIP(c, hipMemcpyAsync(c->h_ticks, c->ps.ticks, (kPersistRounds + 1) * sizeof(long long), hipMemcpyDeviceToHost, s));
     } else {
       for (int i = 0; i < chunk; ++i) {
-        launch_round(c, s, nullptr, nullptr);
+        launch_round(c, c->w, s, nullptr, nullptr);
         if (tm && c->timing_rounds && c->n_round_ev < kMaxRoundEvents) SP_HIP(c, hipEventRecord(c->round_ev[c->n_round_ev++], s));
       }
     }
@@ -879,7 +941,7 @@ sp_status sp_debug_dump(sp_ctx* c, int32_t kind, void* stream, const void* x_dev
     case SP_DUMP_SCORE_CUBE: {
       const int64_t cnt = (int64_t)group_count(c) * c->Mmax * c->B;
       hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, (float*)dst_dev, cnt, -1.0f);
-      launch_round(c, s, nullptr, (float*)dst_dev);
+      launch_round(c, c->w, s, nullptr, (float*)dst_dev);
       break;
     }
     case SP_DUMP_LOGITS: {
