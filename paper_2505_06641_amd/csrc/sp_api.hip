@@ -566,7 +566,7 @@ constexpr size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
                   uint32_t* sortkey, float* logits) {
   if (c->mlp_bf16) {
-    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
+    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A + kXcds;   // at least 8 * ceil(tiles / 8): see xcd_tile
 #define SP_LAUNCH_MLP(DUMP, SPLIT)                                                                                \
     hipLaunchKernelGGL((k_score_mlp_bf16<DUMP, SPLIT>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w,          \
                        (const uint16_t*)x, ids, D, wt, sortkey, (const unsigned char*)c->w1p,                    \
@@ -579,7 +579,7 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
     return;
   }
   if (c->mfma_D > 0) {
-    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A;
+    const int grid = (c->n + kMfTile - 1) / kMfTile + c->A + kXcds;   // at least 8 * ceil(tiles / 8): see xcd_tile
     const dim3 blk(kMfThreads);
 #define SP_LAUNCH_MF(DD)                                                                                          \
     do {                                                                                                          \

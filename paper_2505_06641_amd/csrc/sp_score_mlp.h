@@ -58,8 +58,8 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
   static_assert(kL1Units <= SB::kUnits, "a W1 slice must fit in one block buffer");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
-  const int tile = blockIdx.x;
-  if (tile >= w.tile_start[tb.A]) return;
+  const int tile = xcd_tile(blockIdx.x, w.tile_start[tb.A]);
+  if (tile < 0) return;
   const int4 desc = w.tile_desc[tile];
   const int a = desc.x, seg_e = desc.z;
   const int pos = desc.y + wave * 32 + r;

@@ -470,16 +470,15 @@ __device__ __forceinline__ void class_tiles_and_finish(
   float ssum = 0.f;                                      // softmax denominator of this lane's classes
   const int64_t dump_row = (int64_t)id * tb.Cmax;
 
-  // The class tiles are software-pipelined inside every wavefront: an iteration holds the matrix phase
-  // of tile t+1 and the softmax phase of tile t, which do not depend on each other, and the two
-  // wavefronts that share a SIMD take them in opposite order (wavefronts 0..3 matrix phase first,
-  // 4..7 softmax phase first), so that the matrix cores always have a wavefront feeding them while the
-  // other one keeps the vector ALU busy.  One barrier per tile: block t+2 is fetched through registers
-  // in two halves during the iteration and is complete in LDS at its end.
+  // The two wavefronts that share a SIMD take the phases of a class tile in opposite order, so that the
+  // matrix cores always have a wavefront feeding them while the other one keeps the vector ALU busy:
+  // in the iteration that has block T+1 complete in LDS, wavefronts 0..3 ("early") run the matrix phase
+  // and then the softmax phase of tile T+1, wavefronts 4..7 ("late") the softmax phase of tile T (whose
+  // logits they carried over the barrier) and then the matrix phase of tile T+1.  Either way a wavefront
+  // holds one logit tile at a time.  One barrier per tile: block T+2 is fetched through registers in two
+  // halves during the iteration and is complete in LDS at its end.
   const bool late = wave >= kMfWaves / 2;
-  f32x16 acc, accn;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) accn[v] = 0.f;
+  f32x16 acc;
   StageRegs<D> stg;
   stg.v[0] = stg.v[1] = stg.v[2] = f32x4{0.f, 0.f, 0.f, 0.f};
   // block 1 has to be in LDS before the first iteration reads it
@@ -489,6 +488,9 @@ __device__ __forceinline__ void class_tiles_and_finish(
     logits_phase<D>(buf_a, xh, xl, acc, lane);
     stage_park<D, 0>(buf_b, stg, tid);
     stage_fetch<D, 1>(nsrc, stg, tid);
+    if (!late)
+      softmax_phase<D, DUMP, SPLIT>(buf_a, acc, unscale, ea_lo, ea_hi, ssum, m2, 0, C, g, lane, valid, dump_row,
+                                    logits_out, best_z, best_c);
     stage_park<D, 1>(buf_b, stg, tid);
     __syncthreads();
   }
@@ -498,20 +500,20 @@ __device__ __forceinline__ void class_tiles_and_finish(
     const float4* nsrc = src + (size_t)((T) + 2 < CT ? (T) + 2 : CT - 1) * SB::kUnits;                        \
     stage_fetch<D, 0>(nsrc, stg, tid);                                                                         \
     if (!late) {                                                                                               \
-      if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
+      if (more) logits_phase<D>(NXT, xh, xl, acc, lane);                                                       \
       stage_park<D, 0>(FILL, stg, tid);   /* (past the last block: a copy nobody reads) */                     \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
-      softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, ea_lo, ea_hi, ssum, m2, (T), C, g, lane, valid,        \
-                                    dump_row, logits_out, best_z, best_c);                                     \
+      if (more)                                                                                                \
+        softmax_phase<D, DUMP, SPLIT>(NXT, acc, unscale, ea_lo, ea_hi, ssum, m2, (T) + 1, C, g, lane, valid,  \
+                                      dump_row, logits_out, best_z, best_c);                                   \
     } else {                                                                                                   \
       softmax_phase<D, DUMP, SPLIT>(CUR, acc, unscale, ea_lo, ea_hi, ssum, m2, (T), C, g, lane, valid,        \
                                     dump_row, logits_out, best_z, best_c);                                     \
       stage_park<D, 0>(FILL, stg, tid);                                                                        \
       stage_fetch<D, 1>(nsrc, stg, tid);                                                                       \
-      if (more) logits_phase<D>(NXT, xh, xl, accn, lane);                                                      \
+      if (more) logits_phase<D>(NXT, xh, xl, acc, lane);                                                       \
     }                                                                                                          \
     stage_park<D, 1>(FILL, stg, tid);                                                                          \
-    acc = accn;                                                                                                \
     __syncthreads();                       /* block T+2 is complete in LDS, blocks T and T+1 are free */       \
   }
   for (int t0 = 0; t0 < CT; t0 += 3) {
@@ -617,6 +619,17 @@ __device__ __forceinline__ float load_split_features(const float* __restrict__ x
   return unscale;
 }
 
+// Which scoring tile a workgroup takes.  Consecutive workgroup ids go to the chip's eight accelerator dies
+// (XCDs) in turn, each with an L2 of its own; tiles are ordered by application, so giving every die one
+// contiguous eighth of the tiles lets each application's packed blocks live in one L2 instead of eight.
+// The launch must hold at least 8 * ceil(n_tiles / 8) workgroups; returns -1 for a workgroup without a tile.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int xcd_tile(int wg, int n_tiles) {
+  const int per = (n_tiles + kXcds - 1) / kXcds;
+  const int j = wg / kXcds, tile = (wg % kXcds) * per + j;
+  return (j < per && tile < n_tiles) ? tile : -1;
+}
+
 template <int D, bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
@@ -631,8 +644,8 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   __shared__ float4 buf_c[SB::kUnits];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31;
-  const int tile = blockIdx.x;
-  if (tile >= w.tile_start[tb.A]) return;
+  const int tile = xcd_tile(blockIdx.x, w.tile_start[tb.A]);
+  if (tile < 0) return;
   const int4 desc = w.tile_desc[tile];
   const int a = desc.x, seg_e = desc.z;
   const int pos = desc.y + wave * 32 + r;
