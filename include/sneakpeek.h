@@ -58,9 +58,9 @@ typedef enum { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
 
 /*
  * Registered applications (Sec. 2.2 "System Model", Sec. 3.2): per
- * application a SneakPeek head, the per-class accuracy (recall) of every
- * model variant "for every possible target label", and each variant's
- * profiled latency per batch size.  HOST pointers; sp_create copies
+ * application a SneakPeek head, the accuracy (recall) of every model variant
+ * on each of the application's classes, and each variant's profiled latency
+ * per batch size.  HOST pointers; sp_create copies
  * everything, the caller keeps ownership.
  *
  * Head of application a: hidden_dim == 0 -> logistic, z = x W1 + b1 with
@@ -124,8 +124,10 @@ typedef struct {
   int32_t n_rounds_timed;  /* rounds with an individual time (see sp_get_round_times)          */
 } sp_timing;
 
-/* Validate and upload a profile to `device_id`, allocate window buffers for
- * max_requests.  SP_EINVAL: NULL pointers, counts out of range, acc outside
+/* Application registration (Sec. 3.2 "System Architecture": owners upload
+ * their variants with accuracy and latency profiles before any request is
+ * served).  Validate and upload a profile to `device_id`, allocate window
+ * buffers for max_requests.  SP_EINVAL: NULL pointers, counts out of range, acc outside
  * [0,1] or NaN, latency negative / NaN / decreasing in b, unknown enum,
  * T_d <= 0.  SP_ECAPACITY: beyond the SP_MAX_* limits.  On success *out owns
  * device memory until sp_destroy.                                              */
@@ -153,7 +155,9 @@ sp_status sp_score(sp_ctx* ctx, int32_t n, const void* x_dev, const int32_t* app
                    const float* deadline_ms_dev, const float* weight_dev, void* stream,
                    float* ea_out_dev, float* key_out_dev);
 
-/* One greedy round at the current clock t: a request is live while pending
+/* One greedy round at the current clock t (one pass of Alg. 1's loop over
+ * groups, Sec. 5.2, with the batch as the unit: choice by eq. (13), utility
+ * eq. (2), clock eq. (1)): a request is live while pending
  * and its penalty on the earliest possible completion t + min_m L[a][m][1] is
  * below 1; for every application the first min(B, n_live) live requests in
  * service order form the candidate window; every (a, m, b) is scored and the
@@ -275,8 +279,8 @@ typedef struct {
 sp_status sp_set_policy(sp_ctx* ctx, const sp_policy* policy);
 
 /*
- * Swap-in cost of the variants of one application (Sec. 3.1: a variant's latency "including any context
- * switch time"; Sec. 5.2: grouping exploits model locality and avoids swapping models in and out).
+ * Swap-in cost of the variants of one application (Sec. 3.1 counts the cost of switching to a variant as
+ * part of its latency; Sec. 5.2: grouping keeps a loaded variant in use).
  * swap_ms_host: HOST pointer to M_a values >= 0 (copied), or NULL for none.  A batch on variant m of that
  * application then completes at t + swap_ms[m] + L[a][m][b] unless the previous batch of the window ran
  * the same variant of the same application, in which case it completes at t + L[a][m][b]; candidates are
@@ -293,22 +297,24 @@ const char* sp_last_hip_error(const sp_ctx* ctx);
 /* max_a M_a and max_a C_a of the profile (row widths of the outputs). */
 int32_t sp_max_models(const sp_ctx* ctx);
 int32_t sp_max_classes(const sp_ctx* ctx);
-/* How sp_schedule runs the greedy rounds (Alg. 1, Sec. 5.1.1) on this context: 1 = all rounds of a chunk in
+/* How sp_schedule runs the greedy rounds (Alg. 1, Sec. 5.2) on this context: 1 = all rounds of a chunk in
  * one launch (every (application, variant) pair fits on the device at once), 0 = two kernels
  * per round.  The decisions are the same either way.  sp_greedy_round always takes the second way. */
 int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 
 /*
- * Test hook, not on the hot path.  The one-launch rounds kernel (Alg. 1's rounds, Sec. 5.1.1) tags the words
+ * Test hook, not on the hot path (implements nothing of the paper).  The one-launch rounds kernel tags the words
  * its workgroups exchange with a round generation number that grows by one per round over the life of the
  * context and starts over, with the exchange buffers cleared, before it would exceed 2^23 - 1 (after some
  * eight million rounds).  This sets the number of generations used so far, so that a test can place a window
- * across that point.  Call it between windows only.  SP_EINVAL: ctx NULL or generation >= 2^23 - 1.
+ * across that point, and clears the exchange buffers (words tagged by earlier launches can then never match a
+ * generation that is handed out again).  Synchronises the device.  Call it between windows only.
+ * SP_EINVAL: ctx NULL or generation >= 2^23 - 1.
  */
 sp_status sp_debug_set_generation(sp_ctx* ctx, uint32_t generation);
 
 /*
- * Test hook, not on the hot path.  The workgroups of the one-launch rounds kernel wait for each other with
+ * Test hook, not on the hot path (implements nothing of the paper).  The workgroups of the one-launch rounds kernel wait for each other with
  * bounded polling; a wait that runs out (the device is shared with other long-running work and the grid is
  * not resident as a whole) makes every workgroup leave, sp_schedule return SP_EDEVICE, and the context use
  * two kernels per round from then on (the window has to be scored again).  polls > 0 shortens the bound so
@@ -318,9 +324,8 @@ sp_status sp_debug_set_generation(sp_ctx* ctx, uint32_t generation);
 sp_status sp_debug_set_spin_limit(sp_ctx* ctx, int32_t polls);
 
 /*
- * Diagnostic, not on the hot path: the rate at which the device's matrix cores run the half-precision
- * instruction the scoring kernel is built on (posterior of Def. 4.1.2 and the contraction of Sec. 4.1
- * eq. (9)) when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.
+ * Diagnostic, not on the hot path and no part of the paper's method: the rate at which the device's matrix
+ * cores run the half-precision instruction the scoring kernel is built on when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.
  * The clock the device sustains depends on how many operand bits toggle, so the second figure is the
  * ceiling a kernel fed with real data can reach.  iters in [1, 2^20]: instructions per wavefront = 8 * iters
  * (2048 wavefronts, two per SIMD).  stream: a hipStream_t.  tflops_out (HOST, required): 2 * 32 * 32 * 16 flops per

@@ -275,9 +275,9 @@ class Window:
         self.order = service_order(self.gid, self.omega, self.G)
         self.lat = [widen(l) for l in profile.lat_ms]
         self.lmin = [float(l[:, 0].min()) for l in self.lat]
-        # cost of bringing a variant in (Sec. 3.1: latency "including any context switch time"; Sec. 5.2:
-        # grouping "avoids the additional latency associated with swapping models in and out"): paid by
-        # a batch unless the previous batch of the window ran the same variant of the same application
+        # cost of bringing a variant in (Sec. 3.1 counts switching cost as part of a variant's latency;
+        # Sec. 5.2 groups requests so that a loaded variant is reused): paid by a batch unless the
+        # previous batch of the window ran the same variant of the same application
         swap = getattr(profile, "swap_ms", None)
         self.swap = [None if (swap is None or swap[a] is None) else widen(swap[a]) for a in range(int(profile.n_apps))]
         self.resident = None                 # (application, variant) of the last committed batch

@@ -1115,6 +1115,17 @@ sp_status sp_debug_set_spin_limit(sp_ctx* c, int32_t polls) {
 
 sp_status sp_debug_set_generation(sp_ctx* c, uint32_t generation) {
   if (!c || generation >= kGenMask) return SP_EINVAL;
+  if (c->persist) {
+    // words tagged by earlier launches must not match a generation that is handed out again
+    DeviceGuard g(c->device);
+    if (!g.ok) return SP_EDEVICE;
+    SP_HIP(c, hipDeviceSynchronize());
+    fill_u64(nullptr, c->ps.slots, 8 * (size_t)c->ps.n_pairs);
+    fill_u64(nullptr, c->ps.decision, 8);
+    fill_u64(nullptr, c->ps.ring, (size_t)kPersistRounds * c->A * c->B);
+    fill_u64(nullptr, c->ps.dec, kPersistRounds);
+    SP_HIP(c, hipDeviceSynchronize());
+  }
   c->gen_base = generation;
   return SP_OK;
 }

@@ -65,7 +65,7 @@ __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w
   if (!(Di > 0.f)) err |= kErrDeadline;
   if (!(wi >= 0.f)) err |= kErrWeight;
   if (err) atomicOr(&w.st->err, err);
-  float key = wi * (1.0f + var) * expf(-Di * tb.inv_timescale);
+  float key = fabsf(wi * (1.0f + var) * expf(-Di * tb.inv_timescale));   // a weight of -0 must not give the key -0: its bits would sort first
   w.key[id] = key;
   sortkey[pos] = tb.pol_edf ? __float_as_uint(Di) : ~__float_as_uint(key);   // ascending deadline, or descending key
   w.rec_g[pos] = make_float4(__int_as_float(id), Di, wi, 0.f);   // what the ordering needs of this request, in one piece

@@ -295,7 +295,7 @@ def tiny(seed: int, n: int, classes=(3,), models=(2,), max_batch=4, feat_dim=4, 
 
 
 def attach_priors(profile: Profile, seed: int, kinds=("jeffreys", "weak", "strong", None), window: int = 24) -> Profile:
-    """Gives every application a prior of the kinds Sec. 6.4 compares, cycling through `kinds`:
+    """Gives every application a prior of the kinds Sec. 6.3.3 ("Choice of Prior") compares, cycling through `kinds`:
     "jeffreys" alpha_c = 0.5; "weak" alpha = an expected label frequency vector; "strong" alpha =
     expected label counts in a scheduling window of `window` requests; None = no prior.  The evidence
     weight k is drawn from {1, 5, 10, 20}.  Seeded; holds no arithmetic of the method."""
