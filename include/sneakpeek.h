@@ -325,16 +325,29 @@ sp_status sp_debug_set_spin_limit(sp_ctx* ctx, int32_t polls);
 
 /*
  * Diagnostic, not on the hot path and no part of the paper's method: the rate at which the device's matrix
- * cores run the half-precision instruction the scoring kernel is built on when nothing else competes.  random_bits = 0: constant operands; 1: operands with random bits.
- * The clock the device sustains depends on how many operand bits toggle, so the second figure is the
- * ceiling a kernel fed with real data can reach.  iters in [1, 2^20]: instructions per wavefront = 8 * iters
- * (2048 wavefronts, two per SIMD).  stream: a hipStream_t.  tflops_out (HOST, required): 2 * 32 * 32 * 16 flops per
+ * cores run the half-precision instruction the scoring kernel is built on when nothing else competes.
+ * random_bits = 0: constant operands; 1: operands with random bits.  idle in {0, 1, 2, 4, 8}: after every
+ * eight instructions a wavefront sleeps idle * 64 cycles (idle > 0 runs one wavefront per SIMD, so that
+ * eight instructions are 256 busy cycles of the matrix core: duty cycle 256 / (256 + 64 idle); idle = 0
+ * runs two wavefronts per SIMD back to back).  The clock the device sustains depends on how many operand
+ * bits toggle and on the duty cycle (the instruction runs under a power limit), so the figures with
+ * random bits are the ceiling a kernel fed with real data can reach.  iters in [1, 2^20]: instructions per
+ * wavefront = 8 * iters.  stream: a hipStream_t.  tflops_out (HOST, required): 2 * 32 * 32 * 16 flops per
  * instruction over the time of one launch between two events; clock_ghz_out (HOST, may be NULL): shader
  * cycles over the constant-rate counter.  Allocates and frees its own small buffers; synchronises the stream.
- * SP_EINVAL: iters out of range or tflops_out NULL; SP_EDEVICE: no such device or a HIP call failed.
+ * SP_EINVAL: iters or idle out of range or tflops_out NULL; SP_EDEVICE: no such device or a HIP call failed.
  */
-sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, void* stream, double* tflops_out,
-                             double* clock_ghz_out);
+sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t idle, int32_t iters, void* stream,
+                             double* tflops_out, double* clock_ghz_out);
+
+/*
+ * Diagnostic, not on the hot path and no part of the paper's method: the memory bandwidth a plain streaming
+ * copy kernel reaches on the device, bytes read plus bytes written per second over four launches between
+ * two events (GB/s, 10^9), for `bytes` bytes each way (a multiple of 16, at most 16 GiB).  Allocates and
+ * frees its two buffers; synchronises the stream.  SP_EINVAL: bytes out of range or gbs_out NULL;
+ * SP_ENOMEM: the buffers do not fit; SP_EDEVICE: no such device or a HIP call failed.
+ */
+sp_status sp_debug_copy_rate(int device_id, int64_t bytes, void* stream, double* gbs_out);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_greedy_round_static", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
+           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_copy_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -117,8 +117,10 @@ def load_library(path: Optional[str] = None):
     lib.sp_debug_set_generation.restype = C.c_int
     lib.sp_debug_set_spin_limit.argtypes = [vp, C.c_int32]
     lib.sp_debug_set_spin_limit.restype = C.c_int
-    lib.sp_debug_mfma_rate.argtypes = [C.c_int, C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.sp_debug_mfma_rate.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.sp_debug_mfma_rate.restype = C.c_int
+    lib.sp_debug_copy_rate.argtypes = [C.c_int, C.c_int64, vp, C.POINTER(C.c_double)]
+    lib.sp_debug_copy_rate.restype = C.c_int
     lib.sp_set_timing.argtypes = [vp, C.c_int32]
     lib.sp_set_timing.restype = C.c_int
     lib.sp_get_timing.argtypes = [vp, C.POINTER(sp_timing)]
@@ -323,14 +325,25 @@ class Context:
         return self._check(rc, "sp_debug_dump")
 
 
-def sp_debug_mfma_rate(random_bits: bool, iters: int = 16384, device: int = 0, stream=None):
+def sp_debug_mfma_rate(random_bits: bool, iters: int = 16384, idle: int = 0, device: int = 0, stream=None):
     """(TFLOP/s, shader clock in GHz) of the bare matrix-core loop; see include/sneakpeek.h."""
     lib = load_library()
     tf, ghz = C.c_double(0.0), C.c_double(0.0)
-    rc = lib.sp_debug_mfma_rate(int(device), int(bool(random_bits)), int(iters), _stream_ptr(stream), C.byref(tf), C.byref(ghz))
+    rc = lib.sp_debug_mfma_rate(int(device), int(bool(random_bits)), int(idle), int(iters), _stream_ptr(stream),
+                                C.byref(tf), C.byref(ghz))
     if rc != SP_OK:
         raise SneakPeekError(rc, "sp_debug_mfma_rate")
     return tf.value, ghz.value
+
+
+def sp_debug_copy_rate(n_bytes: int = 1 << 28, device: int = 0, stream=None):
+    """GB/s (read + written) of a plain streaming copy kernel; see include/sneakpeek.h."""
+    lib = load_library()
+    gbs = C.c_double(0.0)
+    rc = lib.sp_debug_copy_rate(int(device), int(n_bytes), _stream_ptr(stream), C.byref(gbs))
+    if rc != SP_OK:
+        raise SneakPeekError(rc, "sp_debug_copy_rate")
+    return gbs.value
 
 
 def to_device(requests, device="cuda:0"):

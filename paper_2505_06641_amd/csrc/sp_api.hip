@@ -34,11 +34,14 @@ struct sp_ctx {
   int64_t cap = 0;
   uint32_t* bufK[2] = {nullptr, nullptr};
   int32_t* bufV[3] = {nullptr, nullptr, nullptr};
-  uint32_t* scan_tot = nullptr;  // [max(A,1)+1, 256] column totals / bases of the radix scan
-  uint32_t* hist = nullptr;
-  int64_t hist_units = 0;
-  int32_t* seg1 = nullptr;    // [2] single-segment plan for the application pass
-  int32_t* unit1 = nullptr;   // [2]
+  // ordering: digit totals, per-tile published counts and tile descriptors of the radix passes
+  uint32_t* dtot_app = nullptr;      // [2 passes, 1 row, 256] pass(es) over the application ids (one segment)
+  uint32_t* dtot_key = nullptr;      // [kMaxSortPasses, tiles_cap, 256] passes inside the applications' ranges
+  int64_t tiles_cap = 0;             // rows per pass slab of dtot_key, tiles of sort_state and sort_desc
+  unsigned long long* sort_state = nullptr;   // [tiles_cap, 256] generation-tagged words of the running pass
+  int4* sort_desc = nullptr;         // [tiles_cap]
+  uint32_t sort_gen = 0;             // generations handed out so far
+  int32_t* seg1 = nullptr;           // [2] the one-segment plan of the pass over the application ids
   State* h_state = nullptr;   // pinned mirror
   bool scored = false;
   int32_t n = 0;
@@ -140,16 +143,6 @@ sp_status dev_upload(sp_ctx* c, T** out, const std::vector<T>& host) {
   if (s != SP_OK) return s;
   if (!host.empty()) SP_HIP(c, hipMemcpy(*out, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
   return SP_OK;
-}
-
-// Elements per sort unit (one wavefront per unit and pass): about a thousand units, between 256 and
-// kMaxUnit elements each.  Larger units mean fewer rows for the column scans, which is what the passes
-// spend most of their time on at these sizes; smaller ones only pay below a few hundred thousand requests.
-int unit_size_for(int64_t n) {
-  int64_t s = ((n / 1024 + 63) / 64) * 64;
-  if (s < 256) s = 256;
-  if (s > kMaxUnit) s = kMaxUnit;
-  return (int)s;
 }
 
 int app_passes(int A) { return (A + 1 <= 256) ? 1 : ((A + 1 <= 65536) ? 2 : 3); }
@@ -332,11 +325,13 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
     if ((s = dev_alloc(c, &c->bufV[i], N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.id_s, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.rec_g, N)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &c->scan_tot, (size_t)(A + 1) * 256)) != SP_OK) return s;
-  c->hist_units = (int64_t)std::max<size_t>(2048, N / 256) + A + 8;
-  if ((s = dev_alloc(c, &c->hist, (size_t)c->hist_units * 256)) != SP_OK) return s;
+  c->tiles_cap = (int64_t)(N / kSortTile) + A + 2;
+  if ((s = dev_alloc(c, &c->dtot_app, 2 * 256)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->dtot_key, (size_t)kMaxSortPasses * c->tiles_cap * 256)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &c->sort_state, (size_t)c->tiles_cap * 256)) != SP_OK) return s;
+  SP_HIP(c, hipMemset(c->sort_state, 0, (size_t)c->tiles_cap * 256 * sizeof(unsigned long long)));
+  if ((s = dev_alloc(c, &c->sort_desc, (size_t)c->tiles_cap)) != SP_OK) return s;
   if ((s = dev_alloc(c, &c->seg1, 2)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &c->unit1, 2)) != SP_OK) return s;
   SP_HIP(c, hipHostMalloc((void**)&c->h_state, sizeof(State), hipHostMallocDefault));
   std::memset(c->h_state, 0, sizeof(State));
   {
@@ -609,18 +604,20 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
     launch_score_generic<float>(c, s, grid, x, ids, D, wt, sortkey, logits);
 }
 
-// One stable radix pass; (keys, vals) -> (keys_out, vals_out).
-void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int max_units, const uint32_t* keys,
-                const int32_t* vals, int shift, uint32_t* keys_out, int32_t* vals_out) {
-  const int blocks = (max_units + kSortWaves - 1) / kSortWaves;
-  hipLaunchKernelGGL(k_radix_hist, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, shift, c->hist);
-  // a wavefront per digit column once the segments average more than one trip of the narrow scan
-  if (max_units / plan.nseg > 16 * kScanUnroll)
-    hipLaunchKernelGGL(k_radix_scan_cols<64>, dim3(plan.nseg * 64), dim3(256), 0, s, plan, c->hist, c->scan_tot);
-  else
-    hipLaunchKernelGGL(k_radix_scan_cols<16>, dim3(plan.nseg * 16), dim3(256), 0, s, plan, c->hist, c->scan_tot);
-  hipLaunchKernelGGL(k_radix_scatter, dim3(blocks), dim3(kSortWaves * kWave), 0, s, plan, keys, vals, shift,
-                     (const uint32_t*)c->hist, (const uint32_t*)c->scan_tot, keys_out, vals_out);
+// One stable radix pass over the tiles of `plan`; (keys, vals) -> (keys_out, vals_out).
+void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int tiles, const uint32_t* keys, const int32_t* vals,
+                int shift, int clamp_a, const uint32_t* dtot_pass, uint32_t* keys_out, int32_t* vals_out,
+                const SegArgs* fused_segments = nullptr) {
+  if (c->sort_gen == 0xFFFFFFFFu) {                       // generation numbers about to wrap: start over
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((c->tiles_cap * 256 + 255) / 256)), dim3(256), 0, s, c->sort_state,
+                       (int64_t)c->tiles_cap * 256, 0ull);
+    c->sort_gen = 0;
+  }
+  const uint32_t gen = ++c->sort_gen;
+  SegArgs sg{};                                            // seg == null: no segment bookkeeping in this launch
+  if (fused_segments) sg = *fused_segments;
+  hipLaunchKernelGGL(k_radix_pass, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals, shift,
+                     clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w);
 }
 
 // Number of groups of the scored window: the applications, or the non-empty (application, subgroup) pairs.
@@ -644,6 +641,11 @@ sp_status fetch_state(sp_ctx* c, hipStream_t s, bool mirrored = false) {
   SP_HIP(c, hipGetLastError());
   c->rounds_done = c->h_state->round;
   c->done = c->h_state->done != 0;
+  if (c->h_state->err & kErrSortSync) {
+    c->hip_err = "ordering: a look-back between tiles of a radix pass ran out";
+    c->scored = false;
+    return SP_EDEVICE;
+  }
   if (c->h_state->err & kErrSync) {
     // resident workgroups lost each other: leave the exchange buffers clean and stop using that path
     c->hip_err = "rounds kernel: a wait between workgroups ran out";
@@ -715,7 +717,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   c->rounds_done = 0;
   c->done = false;
   const int A = c->A;
-  hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(64), 0, s, w.st, n, unit_size_for(n), c->seg1, c->unit1);
+  hipLaunchKernelGGL(k_reset_state, dim3(1), dim3(256), 0, s, w.st, n, c->seg1, c->dtot_app, 2 * 256);
   const bool tm = c->timing && n > 0;
   c->timed_score = false;
   c->timed_rounds = false;
@@ -723,24 +725,38 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
 
   uint32_t *curK = c->bufK[0], *altK = c->bufK[1];
   int32_t *curV = c->bufV[0], *altV = c->bufV[1];
-  const int unit = unit_size_for(n);
+  const int n_app_passes = app_passes(A);
+  const int tiles2 = n / kSortTile + A;                       // upper bound on the tiles inside the applications' ranges
+  const int64_t slab = c->tiles_cap * 256;                    // words per pass of dtot_key
+  // a single pass over the application ids: every application's count is one of its digit totals
+  SegArgs seg_args{n, A, nullptr, c->dtot_app, score_tile(c), kSortTile, w.seg, w.tile_start, w.unit_start, w.tile_desc,
+                   c->sort_desc};
   if (n > 0) {
-    // requests grouped by application: stable pass(es) over the application id
-    hipLaunchKernelGGL(k_app_keys, dim3((n + 255) / 256), dim3(256), 0, s, n, app_dev, A, curK, w.st);
-    SortPlan whole{c->seg1, c->unit1, 1, unit};
-    const int units1 = (n + unit - 1) / unit;
+    // requests grouped by application: stable pass(es) over the application id, read straight from the
+    // caller's array (ids outside [0, A) become A and raise the error flag)
+    SortPlan whole{c->seg1, nullptr, 1, nullptr};
+    const int tiles1 = (n + kSortTile - 1) / kSortTile;
+    hipLaunchKernelGGL(k_digit_totals, dim3(tiles1), dim3(kSortThreads), 0, s, whole, (const uint32_t*)app_dev, A, 0,
+                       n_app_passes, (int64_t)1, c->dtot_app, c->dtot_key, kMaxSortPasses, (int64_t)tiles2 + 1, c->tiles_cap,
+                       w.st);
+    const uint32_t* kin = (const uint32_t*)app_dev;
     const int32_t* vin = nullptr;
-    for (int p = 0; p < app_passes(A); ++p) {
-      radix_pass(c, s, whole, units1, curK, vin, 8 * p, altK, altV);
+    for (int p = 0; p < n_app_passes; ++p) {
+      // a single pass: the segment bookkeeping (which needs only the ids' digit totals) rides along
+      radix_pass(c, s, whole, tiles1, kin, vin, 8 * p, p == 0 ? A : 0, c->dtot_app + 256 * p, altK, altV,
+                 n_app_passes == 1 ? &seg_args : nullptr);
       std::swap(curK, altK);
       std::swap(curV, altV);
+      kin = curK;
       vin = curV;
     }
   }
-  // a single pass over the application ids leaves every application's count in the scan's digit totals
-  const uint32_t* digit_tot = (n > 0 && app_passes(A) == 1) ? (const uint32_t*)c->scan_tot : nullptr;
-  hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, n, A, (const uint32_t*)curK, digit_tot, score_tile(c), unit,
-                     w.seg, w.tile_start, w.unit_start, w.tile_desc, w);
+  if (n == 0 || n_app_passes > 1) {
+    // no pass to ride along with, or two passes (the segment starts then come from the sorted ids)
+    seg_args.sorted_app = curK;
+    seg_args.digit_tot = nullptr;
+    hipLaunchKernelGGL(k_segments, dim3(1), dim3(256), 0, s, seg_args, w);
+  }
   if (n > 0) {
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;
@@ -749,13 +765,14 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     if (tm) SP_HIP(c, hipEventRecord(c->ev[2], s));
     // service order: inside each application by (key descending, id ascending).  The passes carry
     // positions of the grouped array (identity to start with), the grouped ids stay where they are.
-    SortPlan per_app{w.seg, w.unit_start, A, unit};
-    const int units2 = (n + unit - 1) / unit + A;
+    SortPlan per_app{w.seg, w.unit_start, A, c->sort_desc};
+    hipLaunchKernelGGL(k_digit_totals, dim3(tiles2), dim3(kSortThreads), 0, s, per_app, (const uint32_t*)sortkey, 0, 0, 4,
+                       c->tiles_cap, c->dtot_key, (uint32_t*)nullptr, 0, (int64_t)0, (int64_t)0, w.st);
     uint32_t *k_in = sortkey, *k_out = curK;
     const int32_t* v_in = nullptr;
     int32_t *v_out = altV, *v_spare = c->bufV[2];
     for (int p = 0; p < 4; ++p) {
-      radix_pass(c, s, per_app, units2, k_in, v_in, 8 * p, k_out, v_out);
+      radix_pass(c, s, per_app, tiles2, k_in, v_in, 8 * p, 0, c->dtot_key + slab * p, k_out, v_out);
       std::swap(k_in, k_out);
       v_in = v_out;
       std::swap(v_out, v_spare);
@@ -765,8 +782,10 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       // every application; then the non-empty (application, subgroup) pairs become the rounds' groups
       hipLaunchKernelGGL(k_gather_sub_keys, dim3((n + 255) / 256), dim3(256), 0, s, A, (const int32_t*)w.seg, v_in,
                          (const int32_t*)w.sub_g, k_in);
+      hipLaunchKernelGGL(k_digit_totals, dim3(tiles2), dim3(kSortThreads), 0, s, per_app, (const uint32_t*)k_in, 0, 0,
+                         c->sub_passes, c->tiles_cap, c->dtot_key + slab * 4, (uint32_t*)nullptr, 0, (int64_t)0, (int64_t)0, w.st);
       for (int p = 0; p < c->sub_passes; ++p) {
-        radix_pass(c, s, per_app, units2, k_in, v_in, 8 * p, k_out, v_out);
+        radix_pass(c, s, per_app, tiles2, k_in, v_in, 8 * p, 0, c->dtot_key + slab * (4 + p), k_out, v_out);
         std::swap(k_in, k_out);
         v_in = v_out;
         std::swap(v_out, v_spare);
@@ -1130,9 +1149,10 @@ sp_status sp_debug_set_generation(sp_ctx* c, uint32_t generation) {
   return SP_OK;
 }
 
-sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, void* stream, double* tflops_out,
-                             double* clock_ghz_out) {
+sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t idle, int32_t iters, void* stream,
+                             double* tflops_out, double* clock_ghz_out) {
   if (iters < 1 || iters > (1 << 20) || !tflops_out) return SP_EINVAL;
+  if (idle != 0 && idle != 1 && idle != 2 && idle != 4 && idle != 8) return SP_EINVAL;
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) return SP_EDEVICE;
   DeviceGuard g(device_id);
@@ -1144,19 +1164,30 @@ sp_status sp_debug_mfma_rate(int device_id, int32_t random_bits, int32_t iters, 
   sp_status rc = SP_EDEVICE;
   float ms = 0.f;
   long long h[2] = {0, 0};
+  const int threads = idle > 0 ? kProbeIdleThreads : kProbeThreads;
+  auto launch = [&] {
+    const dim3 grd(kProbeBlocks), blk(threads);
+    switch (idle) {
+      case 0: hipLaunchKernelGGL(k_mfma_rate<0>, grd, blk, 0, s, (int)random_bits, (int)iters, out, clk); break;
+      case 1: hipLaunchKernelGGL(k_mfma_rate<1>, grd, blk, 0, s, (int)random_bits, (int)iters, out, clk); break;
+      case 2: hipLaunchKernelGGL(k_mfma_rate<2>, grd, blk, 0, s, (int)random_bits, (int)iters, out, clk); break;
+      case 4: hipLaunchKernelGGL(k_mfma_rate<4>, grd, blk, 0, s, (int)random_bits, (int)iters, out, clk); break;
+      default: hipLaunchKernelGGL(k_mfma_rate<8>, grd, blk, 0, s, (int)random_bits, (int)iters, out, clk); break;
+    }
+  };
   if (hipMalloc((void**)&out, (size_t)kProbeBlocks * kProbeThreads * sizeof(float)) != hipSuccess) goto end;
   if (hipMalloc((void**)&clk, 2 * sizeof(long long)) != hipSuccess) goto end;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto end;
-  // one untimed launch brings the clocks up, the second is timed
-  hipLaunchKernelGGL(k_mfma_rate, dim3(kProbeBlocks), dim3(kProbeThreads), 0, s, (int)random_bits, (int)iters, out, clk);
+  // one untimed launch brings the clocks to their steady state, the second is timed
+  launch();
   if (hipEventRecord(e0, s) != hipSuccess) goto end;
-  hipLaunchKernelGGL(k_mfma_rate, dim3(kProbeBlocks), dim3(kProbeThreads), 0, s, (int)random_bits, (int)iters, out, clk);
+  launch();
   if (hipEventRecord(e1, s) != hipSuccess) goto end;
   if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) goto end;
   if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) goto end;
   if (hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) goto end;
   // 2 * 32 * 32 * 16 flops per instruction and wavefront
-  *tflops_out = (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * kProbeMfmaPerIter * 32768.0 / ((double)ms * 1e-3) / 1e12;
+  *tflops_out = (double)kProbeBlocks * (threads / 64) * (double)iters * kProbeMfmaPerIter * 32768.0 / ((double)ms * 1e-3) / 1e12;
   if (clock_ghz_out) *clock_ghz_out = h[1] > 0 ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
   rc = SP_OK;
 end:
@@ -1164,6 +1195,39 @@ end:
   if (e1) (void)hipEventDestroy(e1);
   if (out) (void)hipFree(out);
   if (clk) (void)hipFree(clk);
+  return rc;
+}
+
+sp_status sp_debug_copy_rate(int device_id, int64_t bytes, void* stream, double* gbs_out) {
+  if (bytes < 16 || bytes > ((int64_t)1 << 34) || !gbs_out) return SP_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device_id < 0 || device_id >= ndev) return SP_EDEVICE;
+  DeviceGuard g(device_id);
+  if (!g.ok) return SP_EDEVICE;
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t n = bytes / 16;
+  float4 *src = nullptr, *dst = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  sp_status rc = SP_EDEVICE;
+  float ms = 0.f;
+  const unsigned grid = (unsigned)std::min<int64_t>((n + 255) / 256, 256 * 64);
+  if (hipMalloc((void**)&src, (size_t)n * 16) != hipSuccess) { rc = SP_ENOMEM; goto end; }
+  if (hipMalloc((void**)&dst, (size_t)n * 16) != hipSuccess) { rc = SP_ENOMEM; goto end; }
+  if (hipMemsetAsync(src, 1, (size_t)n * 16, s) != hipSuccess) goto end;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto end;
+  hipLaunchKernelGGL(k_copy_rate, dim3(grid), dim3(256), 0, s, (const float4*)src, dst, n);   // untimed: page the buffers in
+  if (hipEventRecord(e0, s) != hipSuccess) goto end;
+  for (int i = 0; i < 4; ++i) hipLaunchKernelGGL(k_copy_rate, dim3(grid), dim3(256), 0, s, (const float4*)src, dst, n);
+  if (hipEventRecord(e1, s) != hipSuccess) goto end;
+  if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) goto end;
+  if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) goto end;
+  *gbs_out = 4.0 * 2.0 * (double)n * 16.0 / ((double)ms * 1e-3) / 1e9;     // bytes read + bytes written
+  rc = SP_OK;
+end:
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (src) (void)hipFree(src);
+  if (dst) (void)hipFree(dst);
   return rc;
 }
 

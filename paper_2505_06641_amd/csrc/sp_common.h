@@ -14,6 +14,7 @@ constexpr uint32_t kErrApp = 1u;
 constexpr uint32_t kErrDeadline = 2u;
 constexpr uint32_t kErrWeight = 4u;
 constexpr uint32_t kErrSync = 8u;       // a bounded wait between resident workgroups ran out
+constexpr uint32_t kErrSortSync = 16u;  // a bounded look-back between tiles of a radix pass ran out
 
 // Immutable per-context tables (device pointers).
 struct Tables {

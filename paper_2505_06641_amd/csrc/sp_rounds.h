@@ -374,12 +374,11 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_commit(Tables tb, Windo
 }
 
 // Window state at the start of a window, and the one-segment plan of the pass over the application ids.
-__global__ void k_reset_state(State* st, int n, int unit, int32_t* seg1, int32_t* unit1) {
+__global__ void k_reset_state(State* st, int n, int32_t* seg1, uint32_t* dtot_app, int dtot_words) {
+  for (int i = threadIdx.x; i < dtot_words; i += blockDim.x) dtot_app[i] = 0u;    // digit totals of the pass(es) over the application ids
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     seg1[0] = 0;
     seg1[1] = n;
-    unit1[0] = 0;
-    unit1[1] = (n + unit - 1) / unit;
     st->t = 0.0; st->total_wu = 0.0; st->total_u = 0.0; st->total_viol = 0.0;
     st->round = 0; st->next_order = 1; st->n_sched = 0; st->done = 0; st->err = 0u; st->pad = 0;
     st->last.app = -1; st->last.model = -1;      // nothing resident yet

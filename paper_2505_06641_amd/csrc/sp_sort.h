@@ -7,14 +7,23 @@
 // deadline (earliest deadline first), and, with data-aware subgroups
 // (Sec. 5.3.2), once or twice more with the subgroup label.
 //
-// The unit of work is one wavefront walking `unit` consecutive elements of one
-// segment 64 at a time, in order; units never straddle segments.  A pass is
-// three kernels: per-unit digit histograms, a scan down every (segment, digit)
-// column, and the scatter, in which every wavefront first redoes the small scan
-// over its segment's 256 column totals, then ranks its elements 64 at a time per
-// digit with ballots (equal digits keep their order) and bumps a
-// wavefront-private running offset table in LDS.  A unit's keys and values are
-// all requested before the first is used.  No inter-workgroup waiting.
+// One kernel per pass.  The unit of work is a tile of kSortTile consecutive
+// elements of one segment, taken by one workgroup; tiles never straddle
+// segments.  A workgroup ranks its elements by digit (ballot matching inside
+// a wavefront, equal digits keep their order; per-wavefront digit counts in
+// LDS, scanned across the wavefronts), publishes its 256 digit counts, and
+// gets the counts of the tiles before it in its segment by looking back
+// through what they have published (a tile publishes first its own counts,
+// then the running prefix, so the walk ends at the first tile that already
+// knows its prefix).  The published words carry the generation number of the
+// pass, so a word is valid exactly when its generation matches: no clearing
+// between passes, no fences.  Where each digit of a segment starts follows
+// from the segment's digit totals, which one small kernel (k_digit_totals)
+// counts for all passes of a sort before the first pass.  The elements go
+// through LDS in sorted order, so that global writes are runs of consecutive
+// addresses per digit rather than single elements.
+// A tile waits only for tiles with a lower index, which the hardware starts
+// no later than itself; every wait is bounded all the same (kErrSortSync).
 #pragma once
 #include "sp_common.h"
 #include "sp_wave.h"
@@ -22,22 +31,21 @@
 
 namespace sp {
 
-constexpr int kSortWaves = 4;
-constexpr int kMaxUnit = 1024;                  // largest sort unit (elements per wavefront and pass)
+constexpr int kSortThreads = 512;
+constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kSortItems = 8;                         // elements per thread
+constexpr int kSortTile = kSortThreads * kSortItems;  // elements per tile
+constexpr int kSortSpinLimit = 1 << 20;               // polls before a look-back is given up
+constexpr uint32_t kSortCountMask = 0x3FFFFFFFu;      // a published word: generation << 32 | status << 30 | count
+constexpr int kLookBack = 8;                          // tiles whose published words are requested together
+constexpr int kMaxSortPasses = 6;                     // four key passes and up to two over subgroup labels
 
 struct SortPlan {
   const int32_t* seg;          // [nseg+1] segment starts
-  const int32_t* unit_start;   // [nseg+1] prefix of units per segment
+  const int32_t* unit_start;   // [nseg+1] prefix of tiles per segment
   int32_t nseg;
-  int32_t unit;                // elements per unit, multiple of 64
+  const int4* desc;            // per tile: (segment, first element, end, first tile of the segment); null = one segment
 };
-
-// Orders this wavefront's LDS accesses around it (compiler fence; the hardware
-// already runs one wavefront's LDS operations in issue order).
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-}
 
 // mask of lanes whose 8-bit digit equals mine
 __device__ __forceinline__ unsigned long long match_digit(uint32_t digit, bool valid) {
@@ -51,95 +59,35 @@ __device__ __forceinline__ unsigned long long match_digit(uint32_t digit, bool v
   return m;
 }
 
-__device__ __forceinline__ bool unit_range(const SortPlan& sp, int u, int& beg, int& end) {
-  if (u >= sp.unit_start[sp.nseg]) return false;
-  const int s = find_segment(sp.unit_start, sp.nseg, u);
-  beg = sp.seg[s] + (u - sp.unit_start[s]) * sp.unit;
-  end = min(beg + sp.unit, sp.seg[s + 1]);
+// This workgroup's tile: segment s, elements [beg, end), first tile of s.  False for a workgroup without one.
+__device__ __forceinline__ bool sort_tile(const SortPlan& sp, int tile, int& s, int& beg, int& end, int& first) {
+  if (sp.desc == nullptr) {
+    const int n = sp.seg[1];
+    s = 0; first = 0;
+    beg = tile * kSortTile;
+    end = min(beg + kSortTile, n);
+    return beg < n;
+  }
+  if (tile >= sp.unit_start[sp.nseg]) return false;
+  const int4 d = sp.desc[tile];
+  s = d.x; beg = d.y; end = d.z; first = d.w;
   return true;
 }
 
-// Clamp application ids into [0, A] (A = "invalid") and flag bad ones.
-__global__ void k_app_keys(int n, const int32_t* __restrict__ app, int A, uint32_t* __restrict__ keys, State* st) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const int a = app[i];
-  const bool ok = a >= 0 && a < A;
-  keys[i] = ok ? (uint32_t)a : (uint32_t)A;
-  if (!ok) atomicOr(&st->err, kErrApp);
+// The key of element i: as stored, or (clamp_a > 0) an application id clamped into [0, A] with A = "invalid".
+__device__ __forceinline__ uint32_t sort_key_at(const uint32_t* __restrict__ keys, int i, int clamp_a, bool& bad) {
+  const uint32_t k = keys[i];
+  if (clamp_a <= 0) return k;
+  const int a = (int)k;
+  const bool ok = a >= 0 && a < clamp_a;
+  bad |= !ok;
+  return ok ? k : (uint32_t)clamp_a;
 }
 
-__global__ __launch_bounds__(kSortWaves* kWave) void k_radix_hist(SortPlan sp, const uint32_t* __restrict__ keys,
-                                                                  int shift, uint32_t* __restrict__ hist) {
-  __shared__ uint32_t cnt[kSortWaves][256];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = lane; i < 256; i += 64) cnt[wave][i] = 0;
-  wave_sync();
-  const int u = blockIdx.x * kSortWaves + wave;
-  int beg = 0, end = 0;
-  const bool have = unit_range(sp, u, beg, end);
-  if (have) {
-    uint32_t kbuf[kMaxUnit / 64];                          // all of the unit's keys in flight together
-#pragma unroll
-    for (int c = 0; c < kMaxUnit / 64; ++c) {
-      const int i = beg + c * 64 + lane;
-      kbuf[c] = i < end ? keys[i] : 0u;
-    }
-#pragma unroll
-    for (int c = 0; c < kMaxUnit / 64; ++c)
-      if (beg + c * 64 + lane < end) atomicAdd(&cnt[wave][(kbuf[c] >> shift) & 255u], 1u);
-    wave_sync();
-    for (int i = lane; i < 256; i += 64) hist[(int64_t)u * 256 + i] = cnt[wave][i];
-  }
-}
-
-// Destination offsets from the per-unit counts, in two small kernels.
-// k_radix_scan_cols: a workgroup takes 256 / LPC digit columns of one segment and turns each column
-// hist[.][digit] of the segment's units into exclusive prefixes down the column (LPC lanes per column, each
-// walking every LPC-th unit) and stores the column totals.  LPC = 16 suits the short segments of the key
-// passes (one trip for up to 256 units); a long segment (the pass over the application ids has a single one)
-// takes a whole wavefront per column, so that 1024 units are still one trip to memory.  The exclusive scan
-// over a segment's 256 totals is cheap enough for every scattering wavefront to redo it for itself
-// (wave_digit_bases), which saves a launch per pass.
-// Offset of (unit u, digit d) = seg[s] + (totals of s before d) + hist[u][d].
-constexpr int kScanUnroll = 16;
 constexpr int kSegTable = 1024;                        // applications whose tile prefixes k_segments keeps in LDS
 
-template <int LPC>
-__global__ __launch_bounds__(256) void k_radix_scan_cols(SortPlan sp, uint32_t* __restrict__ hist,
-                                                         uint32_t* __restrict__ tot /*[nseg,256]*/) {
-  static_assert(LPC == 16 || LPC == 64, "a column is scanned by a row of 16 lanes or by a wavefront");
-  constexpr int kCols = 256 / LPC;                       // digit columns per workgroup
-  constexpr int kGroups = 256 / kCols;                   // workgroups per segment
-  const int s = blockIdx.x / kGroups, dg = blockIdx.x % kGroups;
-  const int col = threadIdx.x / LPC, j = threadIdx.x % LPC;
-  const int dgt = dg * kCols + col;
-  const int u0 = sp.unit_start[s], u1 = sp.unit_start[s + 1];
-  uint32_t carry = 0;                                    // total of the column over the chunks done so far
-  // kScanUnroll chunks per trip: their loads are independent of the carry and go out together, so a
-  // long column costs one memory round trip per kScanUnroll * LPC units instead of one per LPC
-  for (int ub = u0; ub < u1; ub += LPC * kScanUnroll) {
-    uint32_t c[kScanUnroll];
-#pragma unroll
-    for (int q = 0; q < kScanUnroll; ++q) {
-      const int u = ub + q * LPC + j;
-      c[q] = u < u1 ? hist[(int64_t)u * 256 + dgt] : 0u;
-    }
-#pragma unroll
-    for (int q = 0; q < kScanUnroll; ++q) {
-      const int u = ub + q * LPC + j;
-      if (ub + q * LPC < u1) {                           // uniform: the rest of the trip is past the segment
-        const uint32_t incl = wave_scan_incl<LPC == 16>(c[q]);   // LPC lanes per column: a row, or the wavefront
-        if (u < u1) hist[(int64_t)u * 256 + dgt] = carry + incl - c[q];
-        carry += __shfl(incl, LPC - 1, LPC);
-      }
-    }
-  }
-  if (j == 0) tot[(int64_t)s * 256 + dgt] = carry;
-}
-
-// Start of every digit of segment s, given the segment's 256 digit totals: lane l returns the starts of
-// digits 4l .. 4l+3.
+// Start of every digit of a segment, given its 256 digit totals: lane l returns the starts of digits
+// 4l .. 4l+3.
 __device__ __forceinline__ uint4 wave_digit_bases(const uint32_t* __restrict__ tot_s, uint32_t seg_start, int lane) {
   const uint4 t = *reinterpret_cast<const uint4*>(tot_s + 4 * lane);
   const uint32_t mine = t.x + t.y + t.z + t.w;
@@ -152,67 +100,31 @@ __device__ __forceinline__ uint4 wave_digit_bases(const uint32_t* __restrict__ t
   return b;
 }
 
-// vals_in == nullptr means the identity (value = element index).
-__global__ __launch_bounds__(kSortWaves* kWave) void k_radix_scatter(
-    SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift,
-    const uint32_t* __restrict__ offs, const uint32_t* __restrict__ tot, uint32_t* __restrict__ keys_out,
-    int32_t* __restrict__ vals_out) {
-  __shared__ __align__(16) uint32_t run[kSortWaves][256];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int u = blockIdx.x * kSortWaves + wave;
-  int beg = 0, end = 0;
-  const bool have = unit_range(sp, u, beg, end);
-  if (!have) return;   // no block-wide barrier below: wavefronts are independent
-  const int sg = find_segment(sp.unit_start, sp.nseg, u);
-  {
-    const uint4 b = wave_digit_bases(tot + (int64_t)sg * 256, (uint32_t)sp.seg[sg], lane);
-    const uint4 o = *reinterpret_cast<const uint4*>(offs + (int64_t)u * 256 + 4 * lane);
-    *reinterpret_cast<uint4*>(&run[wave][4 * lane]) = make_uint4(o.x + b.x, o.y + b.y, o.z + b.z, o.w + b.w);
-  }
-  wave_sync();
-  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  // the whole unit's keys and values are requested before the first one is used: one trip to memory per
-  // unit instead of one per 64 elements (the ranking below is a dependent chain through LDS)
-  uint32_t kbuf[kMaxUnit / 64];
-  int32_t vbuf[kMaxUnit / 64];
-#pragma unroll
-  for (int c = 0; c < kMaxUnit / 64; ++c) {
-    const int i = beg + c * 64 + lane;
-    kbuf[c] = i < end ? keys_in[i] : 0u;
-    vbuf[c] = i < end ? (vals_in ? vals_in[i] : i) : 0;
-  }
-#pragma unroll
-  for (int c = 0; c < kMaxUnit / 64; ++c) {
-    if (beg + c * 64 >= end) break;                        // uniform
-    const int i = beg + c * 64 + lane;
-    const bool valid = i < end;
-    const uint32_t key = kbuf[c];
-    const int32_t val = vbuf[c];
-    const uint32_t dg = (key >> shift) & 255u;
-    const unsigned long long same = match_digit(dg, valid);
-    const int rank = __popcll(same & lt);
-    // the first lane of each digit group reserves the group's slots, then hands the base to its group
-    const int leader = valid ? (__ffsll((long long)same) - 1) : lane;
-    uint32_t base_off = 0;
-    if (valid && lane == leader) base_off = atomicAdd(&run[wave][dg], (uint32_t)__popcll(same));
-    base_off = __shfl(base_off, leader);
-    const uint32_t dst = base_off + (uint32_t)rank;
-    if (valid) {
-      keys_out[dst] = key;
-      vals_out[dst] = val;
-    }
-  }
-}
-
 // Segment starts from the application-sorted keys (values in [0, A], A =
 // invalid): seg[a] = first position with key >= a; then the prefixes of
 // scoring tiles and sort units per application and the scoring tiles' descriptors.  One workgroup.
 // digit_tot, when given, holds the count of every digit of a single radix pass over the application ids
 // (wavefront 0 turns them into the segment starts without any search).
-__global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* __restrict__ sorted_app,
-                                                  const uint32_t* __restrict__ digit_tot, int tile, int unit,
-                                                  int32_t* seg, int32_t* tile_start, int32_t* unit_start,
-                                                  int4* tile_desc, Window w) {
+struct SegArgs {
+  int32_t n, A;
+  const uint32_t* sorted_app;   // application-sorted keys (used when digit_tot is null)
+  const uint32_t* digit_tot;    // or: the count of every application id (one radix pass over the ids)
+  int32_t tile, unit;           // requests per scoring tile and per sort tile
+  int32_t* seg;
+  int32_t* tile_start;
+  int32_t* unit_start;
+  int4* tile_desc;
+  int4* sort_desc;
+};
+
+// Body of k_segments for the first 256 threads of a workgroup (any others only keep the barriers company).
+__device__ __forceinline__ void segments_body(const SegArgs& g, const Window& w) {
+  const int n = g.n, A = g.A, tile = g.tile, unit = g.unit;
+  const uint32_t* __restrict__ sorted_app = g.sorted_app;
+  const uint32_t* __restrict__ digit_tot = g.digit_tot;
+  int32_t *seg = g.seg, *tile_start = g.tile_start, *unit_start = g.unit_start;
+  int4 *tile_desc = g.tile_desc, *sort_desc = g.sort_desc;
+  const bool on = threadIdx.x < 256;
   if (digit_tot != nullptr) {
     if (threadIdx.x < 64) {
       const int lane = threadIdx.x;
@@ -224,7 +136,7 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
       if (lane == 0) seg[A + 1] = n;
     }
   }
-  for (int a = threadIdx.x; a <= A + 1 && digit_tot == nullptr; a += blockDim.x) {
+  for (int a = threadIdx.x; on && a <= A + 1 && digit_tot == nullptr; a += 256) {
     int lo = 0, hi = n;                     // lower_bound(sorted_app, a)
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
@@ -234,7 +146,7 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
   }
   __syncthreads();
   // until (and unless) the requests are split into subgroups, group g is application g
-  for (int a = threadIdx.x; a < A; a += blockDim.x) {
+  for (int a = threadIdx.x; on && a < A; a += 256) {
     w.head[a] = seg[a];
     w.head[w.gcap + a] = seg[a];
     w.grp_app[a] = a;
@@ -244,25 +156,29 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
   // prefixes of tiles and units over the applications: every thread takes a run of consecutive
   // applications, the runs' totals are scanned across the workgroup (launched with 256 threads)
   __shared__ int run_t[256], run_u[256];
-  __shared__ int s_tile[kSegTable + 1], s_seg[kSegTable + 1];   // used when A <= kSegTable
-  const int tid = threadIdx.x;
+  __shared__ int s_tile[kSegTable + 1], s_seg[kSegTable + 1], s_unit[kSegTable + 1];   // used when A <= kSegTable
+  const int tid = on ? threadIdx.x : 0;          // threads beyond 255 shadow thread 0 and store nothing
   const int per = (A + 255) / 256;
-  const int a_lo = min(A, tid * per), a_hi = min(A, a_lo + per);
+  const int a_lo = on ? min(A, tid * per) : 0, a_hi = on ? min(A, a_lo + per) : 0;
   int ts = 0, us = 0;
   for (int a = a_lo; a < a_hi; ++a) {
     const int na = seg[a + 1] - seg[a];
     ts += (na + tile - 1) / tile;
     us += (na + unit - 1) / unit;
   }
-  run_t[tid] = ts;
-  run_u[tid] = us;
+  if (on) {
+    run_t[tid] = ts;
+    run_u[tid] = us;
+  }
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {
     const int t_up = tid >= o ? run_t[tid - o] : 0;
     const int u_up = tid >= o ? run_u[tid - o] : 0;
     __syncthreads();
-    run_t[tid] += t_up;
-    run_u[tid] += u_up;
+    if (on) {
+      run_t[tid] += t_up;
+      run_u[tid] += u_up;
+    }
     __syncthreads();
   }
   const int ts0 = run_t[tid] - ts, us0 = run_u[tid] - us;   // exclusive prefixes of this thread's run
@@ -275,16 +191,18 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
     const int sb = seg[a], na = seg[a + 1] - sb;
     if (table) {
       s_tile[a] = ts;
+      s_unit[a] = us;
       s_seg[a] = sb;
     }
     ts += (na + tile - 1) / tile;
     us += (na + unit - 1) / unit;
   }
-  if (tid == 255) {
+  if (on && tid == 255) {
     tile_start[A] = run_t[255];
     unit_start[A] = run_u[255];
     if (table) {
       s_tile[A] = run_t[255];
+      s_unit[A] = run_u[255];
       s_seg[A] = seg[A];
     }
   }
@@ -293,7 +211,7 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
   if (table) {
     // few applications: every thread places tiles by searching the prefixes in LDS
     const int n_tiles = s_tile[A];
-    for (int t = tid; t < n_tiles; t += 256) {
+    for (int t = tid; on && t < n_tiles; t += 256) {
       int lo = 0, hi = A;                                // last a with s_tile[a] <= t (empty applications share a start)
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -301,13 +219,208 @@ __global__ __launch_bounds__(256) void k_segments(int n, int A, const uint32_t* 
       }
       tile_desc[t] = make_int4(lo, s_seg[lo] + (t - s_tile[lo]) * tile, s_seg[lo + 1], 0);
     }
+    // and one per sort tile: (application, first element, end, first tile of the application)
+    const int n_units = s_unit[A];
+    for (int u = tid; on && u < n_units; u += 256) {
+      int lo = 0, hi = A;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (s_unit[mid] <= u) lo = mid; else hi = mid;
+      }
+      const int b0 = s_seg[lo] + (u - s_unit[lo]) * unit;
+      sort_desc[u] = make_int4(lo, b0, min(b0 + unit, s_seg[lo + 1]), s_unit[lo]);
+    }
   } else {
     ts = ts0;
+    us = us0;
     for (int a = a_lo; a < a_hi; ++a) {
-      const int sb = seg[a], se = seg[a + 1], nt = (se - sb + tile - 1) / tile;
+      const int sb = seg[a], se = seg[a + 1], nt = (se - sb + tile - 1) / tile, nu = (se - sb + unit - 1) / unit;
       for (int t = 0; t < nt; ++t) tile_desc[ts + t] = make_int4(a, sb + t * tile, se, 0);
+      for (int u = 0; u < nu; ++u) sort_desc[us + u] = make_int4(a, sb + u * unit, min(sb + (u + 1) * unit, se), us);
       ts += nt;
+      us += nu;
     }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_segments(SegArgs g, Window w) { segments_body(g, w); }
+
+// Digit totals of every segment for n_pass consecutive passes (digits at shift0, shift0 + 8, ...):
+// dtot[(p * tiles_cap + first tile of the segment) * 256 + digit], which must be zero beforehand.  Also
+// clears zero_rows rows of each of zero_passes pass slabs of another totals array (the next sort's).
+__global__ __launch_bounds__(kSortThreads) void k_digit_totals(SortPlan sp, const uint32_t* __restrict__ keys,
+                                                               int clamp_a, int shift0, int n_pass, int64_t tiles_cap,
+                                                               uint32_t* __restrict__ dtot, uint32_t* __restrict__ zero_ptr,
+                                                               int zero_passes, int64_t zero_rows, int64_t zero_cap,
+                                                               State* st) {
+  __shared__ uint32_t h[4][256];
+  const int tid = threadIdx.x;
+  if (zero_ptr != nullptr) {
+    const int64_t per = zero_rows * 256, stride = (int64_t)gridDim.x * kSortThreads;
+    for (int p = 0; p < zero_passes; ++p)
+      for (int64_t i = (int64_t)blockIdx.x * kSortThreads + tid; i < per; i += stride) zero_ptr[p * zero_cap * 256 + i] = 0u;
+  }
+  int s, beg, end, first;
+  if (!sort_tile(sp, blockIdx.x, s, beg, end, first)) return;
+  for (int i = tid; i < 4 * 256; i += kSortThreads) h[0][i] = 0u;
+  __syncthreads();
+  bool bad = false;
+#pragma unroll
+  for (int c = 0; c < kSortItems; ++c) {
+    const int i = beg + c * kSortThreads + tid;
+    if (i < end) {
+      const uint32_t k = sort_key_at(keys, i, clamp_a, bad);
+      for (int p = 0; p < n_pass; ++p) atomicAdd(&h[p][(k >> (shift0 + 8 * p)) & 255u], 1u);
+    }
+  }
+  if (bad) atomicOr(&st->err, kErrApp);
+  __syncthreads();
+  for (int i = tid; i < n_pass * 256; i += kSortThreads) {
+    const uint32_t c = h[0][i];
+    if (c) atomicAdd(&dtot[((int64_t)(i >> 8) * tiles_cap + first) * 256 + (i & 255)], c);
+  }
+}
+
+// Exclusive prefix sums of one value per thread over the first 256 threads of the workgroup (all
+// kSortThreads threads call it; those beyond 255 pass 0 and get the total).
+__device__ __forceinline__ uint32_t scan256_excl(uint32_t v, uint32_t* wave_tot /*[kSortWaves]*/) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_scan_incl(v);
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0;
+  for (int i = 0; i < kSortWaves; ++i) before += i < wave ? wave_tot[i] : 0u;
+  return before + incl - v;
+}
+
+// One stable pass: (keys_in, vals_in) -> (keys_out, vals_out) by the digit at `shift`.  vals_in == nullptr
+// means the identity (value = element index).  dtot_pass: this pass's slab of digit totals.  state:
+// [tiles][256] published words; gen: this launch's generation (never reused while the array lives).
+__global__ __launch_bounds__(kSortThreads) void k_radix_pass(
+    SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift, int clamp_a,
+    const uint32_t* __restrict__ dtot_pass, unsigned long long* __restrict__ state, uint32_t gen, int spin_limit,
+    uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out, State* st, SegArgs sg, Window sw) {
+  // One extra workgroup (sg.seg != null) does k_segments' job beside the pass over the application ids,
+  // which needs nothing but the ids' digit totals: a launch and its trips to memory less per window.
+  if (sg.seg != nullptr && (int)blockIdx.x == (int)gridDim.x - 1) {
+    segments_body(sg, sw);
+    return;
+  }
+  __shared__ uint32_t cnt[kSortWaves][256];      // digit counts per wavefront, then their exclusive prefix over the wavefronts
+  __shared__ uint32_t lstart[256];               // where each digit starts inside the sorted tile
+  __shared__ uint32_t dbase[256];                // global position of the digit's first element of this tile, minus lstart
+  __shared__ uint32_t wave_tot[kSortWaves];
+  __shared__ uint32_t skey[kSortTile];
+  __shared__ int32_t sval[kSortTile];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int s, beg, end, first;
+  if (!sort_tile(sp, blockIdx.x, s, beg, end, first)) return;
+  const int tile = blockIdx.x;
+  for (int i = tid; i < kSortWaves * 256; i += kSortThreads) cnt[0][i] = 0u;
+  // a wavefront takes kSortItems chunks of 64 consecutive elements: all loads go out before the first is used
+  uint32_t key[kSortItems];
+  int32_t val[kSortItems];
+  bool bad = false;
+#pragma unroll
+  for (int c = 0; c < kSortItems; ++c) {
+    const int i = beg + (wave * kSortItems + c) * 64 + lane;
+    key[c] = i < end ? sort_key_at(keys_in, i, clamp_a, bad) : 0u;
+    val[c] = i < end ? (vals_in ? vals_in[i] : i) : 0;
+  }
+  if (bad) atomicOr(&st->err, kErrApp);
+  __syncthreads();
+  // rank inside the wavefront: lanes with my digit ahead of me in this chunk, plus the wavefront's earlier chunks
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  uint32_t rank[kSortItems];
+#pragma unroll
+  for (int c = 0; c < kSortItems; ++c) {
+    const int i = beg + (wave * kSortItems + c) * 64 + lane;
+    const bool valid = i < end;
+    const uint32_t dg = (key[c] >> shift) & 255u;
+    const unsigned long long same = match_digit(dg, valid);
+    const int leader = valid ? (__ffsll((long long)same) - 1) : lane;
+    uint32_t before = 0;
+    if (valid && lane == leader) before = atomicAdd(&cnt[wave][dg], (uint32_t)__popcll(same));
+    before = __shfl(before, leader);
+    rank[c] = before + (uint32_t)__popcll(same & lt);
+  }
+  __syncthreads();
+  // digit counts of the tile; cnt becomes the exclusive prefix over the wavefronts
+  uint32_t mine = 0;
+  if (tid < 256) {
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) {
+      const uint32_t c = cnt[w][tid];
+      cnt[w][tid] = mine;
+      mine += c;
+    }
+  }
+  // tiles before this one in the segment: publish, look back, publish the running prefix
+  uint32_t excl = 0;
+  if (tid < 256) {
+    unsigned long long* slot = state + (size_t)tile * 256 + tid;
+    const unsigned long long tag = (unsigned long long)gen << 32;
+    if (tile == first) {
+      __hip_atomic_store(slot, tag | (2ull << 30) | mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      __hip_atomic_store(slot, tag | (1ull << 30) | mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // Look back a window of tiles at a time: all of the window's words are requested together (one trip
+      // to memory for up to kLookBack tiles), then taken nearest first until one carries a running prefix.
+      bool lost = false, found = false;
+      for (int t2 = tile - 1; t2 >= first && !found && !lost; t2 -= kLookBack) {
+        unsigned long long v[kLookBack];
+#pragma unroll
+        for (int q = 0; q < kLookBack; ++q) {
+          const int t3 = max(t2 - q, first);
+          v[q] = __hip_atomic_load(state + (size_t)t3 * 256 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int q = 0; q < kLookBack; ++q) {
+          if (t2 - q < first || found || lost) continue;
+          unsigned long long w = v[q];
+          for (int k = 0; (uint32_t)(w >> 32) != gen; ++k) {          // not published yet: poll this one
+            if (k >= spin_limit) { lost = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+            w = __hip_atomic_load(state + (size_t)(t2 - q) * 256 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+          if (lost) continue;
+          excl += (uint32_t)w & kSortCountMask;
+          found = ((uint32_t)w >> 30) == 2u;
+        }
+      }
+      if (lost) atomicOr(&st->err, kErrSortSync);     // the counts seen so far keep every write inside the segment
+      __hip_atomic_store(slot, tag | (2ull << 30) | ((excl + mine) & kSortCountMask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  // where the digits start: inside the tile, and in the segment
+  const uint32_t tot = tid < 256 ? dtot_pass[(size_t)first * 256 + tid] : 0u;
+  const uint32_t ls = scan256_excl(mine, wave_tot);
+  const uint32_t gs = scan256_excl(tot, wave_tot);
+  if (tid < 256) {
+    lstart[tid] = ls;
+    dbase[tid] = (uint32_t)sp.seg[s] + gs + excl - ls;
+  }
+  __syncthreads();
+  // into LDS in sorted order
+#pragma unroll
+  for (int c = 0; c < kSortItems; ++c) {
+    const int i = beg + (wave * kSortItems + c) * 64 + lane;
+    if (i < end) {
+      const uint32_t dg = (key[c] >> shift) & 255u;
+      const uint32_t p = lstart[dg] + cnt[wave][dg] + rank[c];
+      skey[p] = key[c];
+      sval[p] = val[c];
+    }
+  }
+  __syncthreads();
+  // and out: neighbouring threads hold neighbouring elements of a digit's run
+  const int n_tile = end - beg;
+  for (int j = tid; j < n_tile; j += kSortThreads) {
+    const uint32_t k = skey[j];
+    const uint32_t dst = dbase[(k >> shift) & 255u] + (uint32_t)j;
+    keys_out[dst] = k;
+    vals_out[dst] = sval[j];
   }
 }
 
