@@ -417,8 +417,20 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
   c->persist = false;
   const int A = p->n_apps;
   std::vector<int32_t> pa, pm;
-  for (int a = 0; a < A; ++a)
-    for (int m = 0; m < p->n_models[a]; ++m) { pa.push_back(a); pm.push_back(m); }
+  {
+    // Which pair a workgroup takes.  Consecutive workgroup ids go to the chip's eight dies in turn, each
+    // with an L2 of its own, and the variants of an application gather the same rows (deadline, key, the
+    // request's line of expected accuracies): the pairs, application-major, are dealt to the dies in
+    // contiguous runs, so that an application's variants share one L2 (two where a run ends inside it).
+    std::vector<int32_t> na, nm;
+    for (int a = 0; a < A; ++a)
+      for (int m = 0; m < p->n_models[a]; ++m) { na.push_back(a); nm.push_back(m); }
+    const size_t np = na.size();
+    pa.resize(np); pm.resize(np);
+    size_t next = 0;
+    for (size_t x = 0; x < (size_t)kXcds; ++x)
+      for (size_t b = x; b < np; b += kXcds, ++next) { pa[b] = na[next]; pm[b] = nm[next]; }
+  }
   const size_t n_pairs = pa.size();
   const size_t ring = (size_t)kPersistRounds * A * c->B;
   if (n_pairs == 0 || n_pairs > (size_t)kMaxPairs || ring > ((size_t)32 << 20)) return SP_OK;

@@ -22,6 +22,7 @@ constexpr int kMlpH = 256;                       // padded hidden width (zero we
 constexpr int kL1Chunk = 64;                     // input channels per W1 slice
 constexpr int kL1Units = (kMlpH / 32) * (kL1Chunk / 16) * 64;   // 16-byte units per slice (2048 = 32 KB)
 constexpr int kL1PerThread = kL1Units / kMfThreads;             // 4
+constexpr int kL1Pre = 4;                                       // weight fragments in flight from LDS per wavefront
 
 // Bytes of one application's packed layer 1: its slices, then the bias padded with zeros to kMlpH floats.
 inline size_t mlp_layer1_bytes(int d) { return (size_t)((d + kL1Chunk - 1) / kL1Chunk) * kL1Units * 16 + kMlpH * sizeof(float); }
@@ -121,14 +122,21 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
         asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(xn[s]) : "v"(p) : "memory");
       }
     }
+    // the slice's 32 weight fragments in the order they are used, each read kL1Pre fragments ahead of the
+    // MFMA that takes it, so that LDS latency and matrix cores overlap inside a wavefront too
+    {
+      constexpr int kSteps = (kMlpH / 32) * (kL1Chunk / 16);
+      f32x4 af[kL1Pre];
 #pragma unroll
-    for (int hb = 0; hb < kMlpH / 32; ++hb) {
+      for (int i = 0; i < kL1Pre; ++i) af[i] = cur[i * 64 + lane];
 #pragma unroll
-      for (int s = 0; s < kL1Chunk / 16; ++s) {
-        const f32x4 af = cur[(hb * 4 + s) * 64 + lane];
-        hacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(xs[s]), hacc[hb], 0, 0, 0);
+      for (int i = 0; i < kSteps; ++i) {
+        const f32x4 a = af[i % kL1Pre];
+        if (i + kL1Pre < kSteps) af[i % kL1Pre] = cur[(i + kL1Pre) * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
+        hacc[i / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(xs[i % 4]), hacc[i / 4], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);   // keep the fragment reads of later hidden blocks from piling up in registers
     }
     asm volatile("s_waitcnt vmcnt(0)"
                  : "+v"(wst[0]), "+v"(wst[1]), "+v"(wst[2]), "+v"(wst[3]), "+v"(xn[0]), "+v"(xn[1]), "+v"(xn[2]), "+v"(xn[3])
