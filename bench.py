@@ -29,16 +29,14 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_MFMA_F16_TFLOPS = 2500.0
 PEAK_VALU_F32_TFLOPS = 157.3
 
-# HBM traffic of the scoring kernel per launch, from hardware counters (rocprofv3 --pmc FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the same counter reads for the 256 MiB copy of --calibrate-copy; the
-# summaries are under profiles/).  A figure is only reported while the kernel sources it was taken on
-# are unchanged (sha256 over the files below).
+# HBM traffic of the scoring kernel per launch comes from hardware counters taken in profiler runs of this
+# same script (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for
+# the 256 MiB copy of --calibrate-copy).  The summaries under profiles/ carry one line per workload,
+#   scoring_kernel_traffic <workload> fetch_bytes=<f> write_bytes=<w> kernel_sources_sha256=<sha>
+# which is read here; a figure is only reported while the kernel sources it was taken on are unchanged
+# (sha256 over the files below), otherwise traffic is null.
 KERNEL_SOURCES = ["sp_common.h", "sp_score_generic.h", "sp_score_split.h", "sp_score_mlp.h"]
-MEASURED_TRAFFIC = {
-    # workload: (fetch bytes + write bytes per launch, sha256 of the kernel sources at that time)
-    "cfg5": (1506.15e6 + 118.57e6, "cad75f14d2cebdec99f48bef117ba5e06a06f0b4ba350a521ba7d9f7f95884a6"),
-    "cfg4": (94.48e6 + 3.73e6, "cad75f14d2cebdec99f48bef117ba5e06a06f0b4ba350a521ba7d9f7f95884a6"),
-}
+PROFILE_FILES = {w: os.path.join("profiles", f"hot_path_{w}_kernel_stats_and_hbm_traffic.md") for w in ("cfg4", "cfg5")}
 
 
 def kernel_sources_sha():
@@ -51,13 +49,23 @@ def kernel_sources_sha():
 
 
 def measured_traffic(workload):
-    ent = MEASURED_TRAFFIC.get(workload)
-    if ent is None:
-        return None
+    """(bytes per launch or None, where the figure comes from)."""
+    rel = PROFILE_FILES.get(workload)
+    if rel is None:
+        return None, None
     try:
-        return ent[0] if kernel_sources_sha() == ent[1] else None
-    except OSError:
-        return None
+        sha = kernel_sources_sha()
+        with open(os.path.join(ROOT, rel)) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 5 and t[0] == "scoring_kernel_traffic" and t[1] == workload:
+                    kv = dict(x.split("=", 1) for x in t[2:])
+                    if kv.get("kernel_sources_sha256") == sha:
+                        return float(kv["fetch_bytes"]) + float(kv["write_bytes"]), rel
+                    return None, rel + " (taken on other kernel sources: not reported)"
+    except (OSError, ValueError, KeyError):
+        pass
+    return None, None
 
 
 def scoring_flops_per_request(p, a):
@@ -67,10 +75,17 @@ def scoring_flops_per_request(p, a):
     return head + 2 * C * M
 
 
-def cpu_baseline(w, n_sample, rounds, policy=None):
-    """The oracle, as it stands, on the first n_sample requests of the same workload."""
+def cpu_baseline(w, n_sample, rounds, policy=None, threads=None):
+    """The oracle, as it stands (NumPy float64; its matrix products run in NumPy's BLAS), on the first
+    n_sample requests of the same workload; threads: None = whatever the BLAS takes, or a limit."""
     from oracle import sneakpeek_oracle as orc
     from paper_2505_06641_amd import workloads as wl
+    if threads is not None:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=int(threads)):
+            out = cpu_baseline(w, n_sample, rounds, policy, None)
+        out["cores"] = int(threads)
+        return out
     try:
         from threadpoolctl import threadpool_info
         cores = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
@@ -94,7 +109,8 @@ def cpu_baseline(w, n_sample, rounds, policy=None):
     cand = float(n_sample) * int(np.max(p.n_models)) * int(p.max_batch)
     return {"value": cand / (t2 - t0), "unit": "candidates/s", "cores": cores, "kind": "oracle",
             "sample": f"first {n_sample} of {rq.n} requests of {w.name} (full profile), scoring {t1 - t0:.2f} s + "
-                      f"{win.round} rounds {t2 - t1:.2f} s, NumPy float64",
+                      f"{win.round} rounds {t2 - t1:.2f} s, NumPy float64 with BLAS matrix products",
+            "implementation": "NumPy/BLAS",
             "round_latency_us": (t2 - t1) / max(1, win.round) * 1e6}
 
 
@@ -161,15 +177,18 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    k_ms, group_ms, order_ms, rounds_ms, round_us = [], [], [], [], []
+    k_ms, group_ms, order_ms, rounds_ms, finish_ms, copy_ms = [], [], [], [], [], []
     n_rounds = 0
+    n_evals = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
         rc, summ, _ = step()
         tm = ctx.sp_get_timing()           # waits only for events that the step has already waited for
         k_ms.append(tm["score_kernel_ms"]); group_ms.append(tm["group_ms"])
         order_ms.append(tm["order_ms"]); rounds_ms.append(tm["rounds_ms"])
+        finish_ms.append(tm["finish_order_ms"]); copy_ms.append(tm["copy_outputs_ms"])
         n_rounds = summ["n_rounds"]
+        n_evals = tm["utility_evaluations"]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     # per-round latencies from one extra, untimed step with an event after every round
@@ -227,10 +246,21 @@ def main():
         tf_const, ghz_const = binding.sp_debug_mfma_rate(False)
         tf_rand, ghz_rand = binding.sp_debug_mfma_rate(True)
         sustained = peak_c * tf_rand / PEAK_MFMA_F16_TFLOPS
+        # the same loop with idle gaps (one wavefront per SIMD: 256 busy cycles, then about 64 * idle idle ones):
+        # under the power limit the clock rises as the duty cycle falls, so the throughput on real data stays
+        # near one level until the clock reaches its maximum
+        duty = []
+        for idle in (1, 2, 4, 8):
+            tf_i, ghz_i = binding.sp_debug_mfma_rate(True, idle=idle)
+            duty.append({"idle": idle, "tflops": tf_i, "clock_ghz": ghz_i,
+                         "duty_cycle": tf_i / (1024 * 1024 * ghz_i * 1e9 / 1e12) if ghz_i > 0 else None})
         roof["mfma_f16_measured"] = {"constant_operands_tflops": tf_const, "constant_operands_clock_ghz": ghz_const,
                                      "random_operands_tflops": tf_rand, "random_operands_clock_ghz": ghz_rand,
-                                     "peak_scaled_to_random_operands": sustained, "frac_of_that": tflops / sustained}
-    roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": measured_traffic(args.workload),
+                                     "peak_scaled_to_random_operands": sustained, "frac_of_that": tflops / sustained,
+                                     "random_operands_with_idle_gaps": duty}
+    traffic, traffic_source = measured_traffic(args.workload)
+    roof.update({"kernel": "fused posterior/EA/key scoring kernel", "kernel_ms": k_avg, "traffic": traffic,
+                 "traffic_source": traffic_source,
                  "peak_note": peak_note, "x_fp32_mfma_peak": tflops / PEAK_MFMA_F32_TFLOPS,
                  "algorithmic_flops": flops, "algorithmic_bytes": k_bytes, "hbm_gbs": gbs, "tflops": tflops})
 
@@ -254,10 +284,35 @@ def main():
                      "order_by_key": float(np.mean(order_ms)), "rounds": float(np.mean(rounds_ms))},
         "roofline": roof,
     }
+    # utility evaluations the rounds really performed (per round and (group, variant): nb (nb + 1) / 2 terms
+    # for a candidate window of nb requests), counted by the kernels themselves
+    r_ms = float(np.mean(rounds_ms))
+    out["utility_evaluations"] = {"per_step": int(n_evals), "per_round_mean": float(n_evals) / max(1, n_rounds),
+                                  "per_s": float(n_evals) / (r_ms * 1e-3) if r_ms > 0 else None}
+    # the streaming stages against the HBM roofline: algorithmic bytes (what each has to read and write,
+    # 4-byte ids / keys / positions) over the stage time from HIP events
+    N = float(n)
+    g_ms, o_ms, f_ms, c_ms = float(np.mean(group_ms)), float(np.mean(order_ms)), float(np.mean(finish_ms)), float(np.mean(copy_ms))
+
+    def stream(name, nbytes, ms, note):
+        gbs_ = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None
+        return {"name": name, "algorithmic_bytes": nbytes, "ms": ms, "gbs": gbs_,
+                "frac_of_hbm_peak": gbs_ / PEAK_HBM_GBS if gbs_ else None, "what": note}
+    out["kernels"] = [
+        stream("group_by_app", 16 * N, g_ms, "digit totals of the application ids (4 B read per request) + one radix pass (4 B read, 8 B written)"),
+        stream("order_by_key_passes", 68 * N, o_ms - f_ms, "digit totals of the keys (4 B) + four radix passes (8 B read, 8 B written each)"),
+        stream("finish_order", 57 * N, f_ms, "position, 16-byte record and key read; id, deadline, weight, key, pending flag written; outputs reset"),
+        stream("copy_outputs", 32 * N, c_ms, "four per-request outputs read and written"),
+    ]
+    out["hbm_copy_measured_gbs"] = binding.sp_debug_copy_rate(1 << 28)
     if not args.no_cpu_baseline:
         default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 65536, "cfg5": 1048576}[args.workload]
         ns = min(n, args.cpu_sample or default_sample)
         out["cpu_baseline"] = cpu_baseline(w, ns, rounds, policy)
+        # and on one thread, on a sixteenth of that sample at the largest sizes so that it stays within seconds
+        ns1 = ns if ns <= 65536 else ns // 16
+        one = cpu_baseline(w, ns1, rounds, policy, threads=1)
+        out["cpu_baseline"]["one_thread"] = {k: one[k] for k in ("value", "unit", "cores", "sample", "round_latency_us")}
     ctx.close()
     print(json.dumps(out))
 

@@ -122,6 +122,13 @@ typedef struct {
   float order_ms;          /* per-application ordering by key                                  */
   float rounds_ms;         /* all rounds of the last sp_schedule call                          */
   int32_t n_rounds_timed;  /* rounds with an individual time (see sp_get_round_times)          */
+  float finish_order_ms;   /* within order_ms: the kernel that gathers id, deadline, weight and
+                              key per service position after the last radix pass              */
+  float copy_outputs_ms;   /* the kernel that copies the four per-request outputs to the
+                              caller's arrays (first chunk of the last sp_schedule call)      */
+  int64_t utility_evaluations;  /* terms key * EA * (1 - penalty) summed by the rounds of the
+                              window so far: per round and (group, variant), nb (nb + 1) / 2
+                              for a candidate window of nb requests (nb under SP_BATCH_WHOLE) */
 } sp_timing;
 
 /* Application registration (Sec. 3.2 "System Architecture": owners upload
@@ -327,9 +334,10 @@ sp_status sp_debug_set_spin_limit(sp_ctx* ctx, int32_t polls);
  * Diagnostic, not on the hot path and no part of the paper's method: the rate at which the device's matrix
  * cores run the half-precision instruction the scoring kernel is built on when nothing else competes.
  * random_bits = 0: constant operands; 1: operands with random bits.  idle in {0, 1, 2, 4, 8}: after every
- * eight instructions a wavefront sleeps idle * 64 cycles (idle > 0 runs one wavefront per SIMD, so that
- * eight instructions are 256 busy cycles of the matrix core: duty cycle 256 / (256 + 64 idle); idle = 0
- * runs two wavefronts per SIMD back to back).  The clock the device sustains depends on how many operand
+ * eight instructions a wavefront sleeps about idle * 64 cycles (idle > 0 runs one wavefront per SIMD, so that
+ * eight instructions are 256 busy cycles of the matrix core followed by the gap; the duty cycle reached is
+ * tflops_out over 1024 SIMDs * 1024 flops per cycle * the clock; idle = 0 runs two wavefronts per SIMD back
+ * to back).  The clock the device sustains depends on how many operand
  * bits toggle and on the duty cycle (the instruction runs under a power limit), so the figures with
  * random bits are the ceiling a kernel fed with real data can reach.  iters in [1, 2^20]: instructions per
  * wavefront = 8 * iters.  stream: a hipStream_t.  tflops_out (HOST, required): 2 * 32 * 32 * 16 flops per

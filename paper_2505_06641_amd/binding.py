@@ -62,7 +62,8 @@ class sp_summary(C.Structure):
 
 class sp_timing(C.Structure):
     _fields_ = [("group_ms", C.c_float), ("score_kernel_ms", C.c_float), ("order_ms", C.c_float),
-                ("rounds_ms", C.c_float), ("n_rounds_timed", C.c_int32)]
+                ("rounds_ms", C.c_float), ("n_rounds_timed", C.c_int32), ("finish_order_ms", C.c_float),
+                ("copy_outputs_ms", C.c_float), ("utility_evaluations", C.c_int64)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

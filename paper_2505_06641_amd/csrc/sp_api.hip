@@ -82,7 +82,9 @@ struct sp_ctx {
   bool timing = false;
   bool timing_rounds = false;
   bool timed_score = false, timed_rounds = false;
-  hipEvent_t ev[6] = {};                 // group start, score start, score stop, order stop, rounds start, rounds stop
+  hipEvent_t ev[9] = {};                 // group start, score start, score stop, order stop, rounds start, rounds stop,
+                                         // finish-order start, copy-outputs start and stop
+  bool timed_copy = false;
   std::vector<hipEvent_t> round_ev;      // one after each timed round
   int n_round_ev = 0;
 };
@@ -803,6 +805,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
         std::swap(v_out, v_spare);
       }
     }
+    if (tm) SP_HIP(c, hipEventRecord(c->ev[6], s));
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
                        (const uint32_t*)k_in, w, c->tb.pol_edf | c->tb.pol_split);
     if (c->tb.pol_split) {
@@ -892,6 +895,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   const bool tm = c->timing;
   c->n_round_ev = 0;
   c->timed_rounds = false;
+  c->timed_copy = false;
   if (tm) SP_HIP(c, hipEventRecord(c->ev[4], s));
   c->round_ms.clear();
   while (!c->done) {
@@ -914,8 +918,14 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
     // the per-request outputs go out right behind the rounds, so that the one host synchronisation of
     // fetch_state covers them too (a later chunk simply copies again)
     if (c->n > 0 && (model_out_dev || round_out_dev || order_out_dev || util_out_dev)) {
+      const bool tc = tm && !outputs_copied;
+      if (tc) SP_HIP(c, hipEventRecord(c->ev[7], s));
       hipLaunchKernelGGL(k_copy_outputs, dim3((c->n + 255) / 256), dim3(256), 0, s, c->n, c->w, model_out_dev,
                          round_out_dev, order_out_dev, util_out_dev);
+      if (tc) {
+        SP_HIP(c, hipEventRecord(c->ev[8], s));
+        c->timed_copy = true;
+      }
       outputs_copied = true;
     }
     st = fetch_state(c, s);          // tells how far the device got and whether the queue ran dry
@@ -1018,11 +1028,17 @@ sp_status sp_get_timing(sp_ctx* c, sp_timing* out) {
     SP_HIP(c, hipEventElapsedTime(&t.group_ms, c->ev[0], c->ev[1]));
     SP_HIP(c, hipEventElapsedTime(&t.score_kernel_ms, c->ev[1], c->ev[2]));
     SP_HIP(c, hipEventElapsedTime(&t.order_ms, c->ev[2], c->ev[3]));
+    SP_HIP(c, hipEventElapsedTime(&t.finish_order_ms, c->ev[6], c->ev[3]));
   }
   if (c->timed_rounds) {
     SP_HIP(c, hipEventSynchronize(c->ev[5]));
     SP_HIP(c, hipEventElapsedTime(&t.rounds_ms, c->ev[4], c->ev[5]));
     t.n_rounds_timed = c->round_ms.empty() ? std::min(c->n_round_ev, c->rounds_in_call) : (int32_t)c->round_ms.size();
+    if (c->timed_copy) {
+      SP_HIP(c, hipEventSynchronize(c->ev[8]));
+      SP_HIP(c, hipEventElapsedTime(&t.copy_outputs_ms, c->ev[7], c->ev[8]));
+    }
+    t.utility_evaluations = (int64_t)c->h_state->n_evals;
   }
   *out = t;
   return SP_OK;

@@ -68,6 +68,7 @@ struct State {
   int32_t done;               // 1 once a round found nothing live
   uint32_t err;               // kErr* bits
   int32_t pad;
+  unsigned long long n_evals; // utility evaluations (terms of the candidates' sums) by the rounds so far
   Decision last;              // the most recent committed batch
 };
 

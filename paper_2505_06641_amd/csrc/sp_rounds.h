@@ -133,6 +133,12 @@ __device__ __forceinline__ unsigned long long triangle_best(int kind, const floa
   return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
 }
 
+// Utility evaluations (terms key * EA * (1 - penalty)) behind the candidates of one (group, variant) pair
+// over a window of nb requests: every batch size b sums its first b requests, or only the whole window does.
+__device__ __forceinline__ unsigned long long triangle_evals(int nb, int whole) {
+  return whole ? (unsigned long long)nb : (unsigned long long)nb * (unsigned long long)(nb + 1) / 2ull;
+}
+
 // Penalty kind the candidates of application a are compared under: its own (eq. 13), or the step penalty
 // when variants are compared by accuracy among those that meet the deadline (Sec. 6.1 "Max Accuracy").
 __device__ __forceinline__ int scoring_penalty(const Tables& tb, int kind) { return tb.pol_max_accuracy ? 0 : kind; }
@@ -162,7 +168,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
   __shared__ int32_t wave_cnt[kRoundThreads / 64];
   __shared__ unsigned long long red[kRoundThreads / 64];
   __shared__ double dsum[kRoundThreads];
-  const State* st = w.st;
+  State* st = w.st;
   if (st->done || st->err) return;
   const int grp = blockIdx.x / tb.Mmax, m = blockIdx.x % tb.Mmax;   // group: an application, or one of its subgroups
   if (grp >= *w.grp_n) return;
@@ -243,6 +249,7 @@ __global__ __launch_bounds__(kRoundThreads) void k_round_score(Tables tb, Window
     return;
   }
   for (int j = tid; j < nb; j += nthr) ent[j] = window_entry(tb, w, win[j], m);
+  if (tid == 0) atomicAdd(&st->n_evals, triangle_evals(nb, tb.pol_whole));
   __syncthreads();
   const float* lat = tb.lat + ((int64_t)a * tb.Mmax + m) * B;
   const double t0 = start_time(tb, st->last, t, a, m);
@@ -381,6 +388,7 @@ __global__ void k_reset_state(State* st, int n, int32_t* seg1, uint32_t* dtot_ap
     seg1[1] = n;
     st->t = 0.0; st->total_wu = 0.0; st->total_u = 0.0; st->total_viol = 0.0;
     st->round = 0; st->next_order = 1; st->n_sched = 0; st->done = 0; st->err = 0u; st->pad = 0;
+    st->n_evals = 0ull;
     st->last.app = -1; st->last.model = -1;      // nothing resident yet
   }
 }

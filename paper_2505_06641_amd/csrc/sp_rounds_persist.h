@@ -256,6 +256,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   double t = st->t;
   int scan_end = w.head[(r & 1) * w.gcap + a];   // everything before it is consumed or dead
   int nb = 0, shift = 0;
+  unsigned long long evals = 0ull;               // utility evaluations of this pair in this launch
   for (int j = tid; j < B; j += kRoundThreads) lat_s[j] = tb.lat[((int64_t)a * tb.Mmax + m) * B + j];
   if (tid == 0) timed_out = 0;
   __syncthreads();
@@ -356,6 +357,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
     // ---- triangle: the same code as k_round_score ----
     unsigned long long best = 0ull;
     const float swap_now = (prev_a == a && prev_m == m) ? 0.f : my_swap;
+    evals += triangle_evals(nbe, tb.pol_whole);
     if (nbe > 0)
       best = triangle_best(scoring_penalty(tb, kind), ent, lat_s, nbe, Bw, t + (double)swap_now,
                            (uint32_t)((a * tb.Mmax + m) * B), nullptr, tb.pol_whole ? nbe : 0);
@@ -417,6 +419,7 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
     prev_a = asel; prev_m = msel;
     r += 1;
   }
+  if (tid == 0 && evals != 0ull) atomicAdd(&st->n_evals, evals);
   // first position of this application that may still be live, for whoever continues the window
   if (m == 0 && tid == 0) w.head[(r & 1) * w.gcap + a] = shift < nb ? win[shift] : scan_end;
 }

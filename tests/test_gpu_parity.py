@@ -705,6 +705,47 @@ def test_matrix_core_rate_diagnostic(gpu):
     with pytest.raises(binding.SneakPeekError) as e:
         binding.sp_debug_mfma_rate(True, iters=0)
     assert e.value.status == binding.SP_EINVAL
+    with pytest.raises(binding.SneakPeekError) as e:
+        binding.sp_debug_mfma_rate(True, iters=64, idle=3)
+    assert e.value.status == binding.SP_EINVAL
+    # with idle gaps (one wavefront per SIMD) the matrix cores cannot be busier than without
+    for idle in (1, 8):
+        tf, ghz = binding.sp_debug_mfma_rate(True, iters=2048, idle=idle)
+        ceiling = 1024 * 32768 / 32 * ghz * 1e9 / 1e12
+        assert 0.05 * ceiling < tf < 1.15 * ceiling
+        if idle == 8:
+            assert tf < 0.6 * ceiling            # 256 busy cycles, then some 512 idle ones
+
+
+def test_copy_rate_diagnostic_and_stage_timing(gpu):
+    torch, binding = gpu
+    gbs = binding.sp_debug_copy_rate(1 << 26)
+    assert 100.0 < gbs < 16000.0                 # read + written; the data sheet says 8,000 GB/s
+    lib = binding.load_library()
+    import ctypes as C
+    out = C.c_double(0.0)
+    assert lib.sp_debug_copy_rate(0, 8, None, C.byref(out)) == binding.SP_EINVAL
+    assert lib.sp_debug_copy_rate(0, 1 << 20, None, None) == binding.SP_EINVAL
+    # the timing record: stage times are consistent, the evaluation count is the triangle's
+    w = wl.tiny(seed=7700, n=600, classes=(4, 3), models=(2, 3), max_batch=7, deadline=(50.0, 90.0))
+    ctx = binding.Context(w.profile, 600)
+    ctx.sp_set_timing(1)
+    x, app, D, wt = binding.to_device(w.requests)
+    model = torch.zeros(600, dtype=torch.int32, device="cuda:0")
+    for one_launch in (True, False):
+        ctx.sp_score(x, app, D, wt)
+        if one_launch:
+            rc, summ, _ = ctx.sp_schedule(3, model_out=model)
+        else:
+            for _ in range(3):
+                ctx.sp_greedy_round()
+            rc, summ, _ = ctx.sp_schedule(0 if False else 1, model_out=model)    # brings the state to the host
+        tm = ctx.sp_get_timing()
+        assert 0.0 < tm["finish_order_ms"] <= tm["order_ms"] and tm["copy_outputs_ms"] > 0.0
+        # loose deadlines: every round sees full windows of 7 requests in both applications
+        rounds = summ["n_rounds"]
+        assert tm["utility_evaluations"] == rounds * (2 + 3) * 7 * 8 // 2
+    ctx.close()
 
 
 def test_a_caller_stream_is_honoured(gpu):
