@@ -280,8 +280,10 @@ typedef struct {
                              (application, subgroup) pair is then a group of its own in the rounds (own service
                              order, own candidate window; batches never mix subgroups; ties go to the smaller
                              (application, subgroup)).  The label uses the head's own softmax output, also when a
-                             prior is set.  SP_ECAPACITY if sum_a (C_a + 1) exceeds 65536.  sp_schedule then runs
-                             two kernels per round, and SP_DUMP_SCORE_CUBE has one [Mmax, B] slab per group.       */
+                             prior is set.  SP_ECAPACITY if sum_a (C_a + 1) exceeds 65536.  SP_DUMP_SCORE_CUBE then
+                             has one [Mmax, B] slab per group.  sp_schedule still runs the rounds in one launch
+                             while no application of the scored window has more than 64 non-empty groups
+                             (sp_rounds_in_one_launch after sp_score tells), else two kernels per round.           */
 } sp_policy;
 sp_status sp_set_policy(sp_ctx* ctx, const sp_policy* policy);
 
@@ -305,8 +307,10 @@ const char* sp_last_hip_error(const sp_ctx* ctx);
 int32_t sp_max_models(const sp_ctx* ctx);
 int32_t sp_max_classes(const sp_ctx* ctx);
 /* How sp_schedule runs the greedy rounds (Alg. 1, Sec. 5.2) on this context: 1 = all rounds of a chunk in
- * one launch (every (application, variant) pair fits on the device at once), 0 = two kernels
- * per round.  The decisions are the same either way.  sp_greedy_round always takes the second way. */
+ * one launch (every (application, variant) pair fits on the device at once and, with group splitting, no
+ * application of the scored window has more than 64 groups: after sp_score the call waits for that count),
+ * 0 = two kernels per round.  The decisions are the same either way.  sp_greedy_round always takes the
+ * second way. */
 int32_t sp_rounds_in_one_launch(const sp_ctx* ctx);
 
 /*

@@ -57,6 +57,7 @@ struct sp_ctx {
   int64_t* w1_off = nullptr;         // [A] byte offsets
   // all rounds of a chunk in one launch, when every (application, variant) pair fits on the device at once
   bool persist = false;
+  bool persist_split = false;        // ... and also with the per-wavefront windows that subgroups need in LDS
   Persist ps{};
   uint32_t gen_base = 0;             // slot generations handed out so far
   int32_t spin_limit = kSpinLimit;   // polls before a wait between resident workgroups is given up
@@ -73,7 +74,7 @@ struct sp_ctx {
   // data-aware group splitting (Sec. 5.3.2): one slot per possible (application, subgroup code)
   int32_t n_slots = 0;
   int32_t *slot_app = nullptr, *slot_base = nullptr, *slot_beg = nullptr, *slot_end = nullptr;
-  int32_t* h_grp_n = nullptr;        // pinned: number of groups of the scored window
+  int32_t* h_grp_n = nullptr;        // pinned [2]: number of groups of the scored window, most groups of one application
   hipEvent_t ev_groups = nullptr;    // recorded after the copy into h_grp_n
   int sub_passes = 0;                // 8-bit radix passes over the subgroup codes
   unsigned char* static_scratch = nullptr;   // this device's copy of the static scratch array (sp_greedy_round_static)
@@ -308,7 +309,7 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   w.sub_g = nullptr;
   if ((s = dev_alloc(c, &w.grp_app, A)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.grp_end, A)) != SP_OK) return s;
-  if ((s = dev_alloc(c, &w.grp_n, 1)) != SP_OK) return s;
+  if ((s = dev_alloc(c, &w.grp_n, 2)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.model, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.round_of, N)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.order_of, N)) != SP_OK) return s;
@@ -438,7 +439,7 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
   if (n_pairs == 0 || n_pairs > (size_t)kMaxPairs || ring > ((size_t)32 << 20)) return SP_OK;
   int cus = 0, per_cu = 0, rate_khz = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) return SP_OK;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent, kRoundThreads, 0) != hipSuccess) {
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent<false>, kRoundThreads, 0) != hipSuccess) {
     (void)hipGetLastError();
     return SP_OK;
   }
@@ -468,6 +469,24 @@ sp_status setup_persist(sp_ctx* c, const sp_profile* p) {
   return SP_OK;
 }
 
+// LDS the resident rounds kernel needs beyond its static arrays: with subgroups, B window entries and B
+// positions per wavefront.
+size_t persist_dynamic_lds(const sp_ctx* c) {
+  return c->tb.pol_split ? (size_t)(kRoundThreads / 64) * (size_t)c->B * (sizeof(float4) + sizeof(int32_t)) : 0;
+}
+
+// Whether sp_schedule runs the rounds of the scored window in one launch: the resident grid fits the device,
+// and with subgroups no application has more groups than a resident workgroup serves (known once the
+// window's groups have been counted on the device).
+bool rounds_in_one_launch(sp_ctx* c) {
+  if (!c->persist) return false;
+  if (!c->tb.pol_split) return true;
+  if (!c->persist_split) return false;
+  if (!c->scored) return true;
+  (void)hipEventSynchronize(c->ev_groups);
+  return c->h_grp_n[1] <= kMaxAppGroups;
+}
+
 void fill_u64(hipStream_t s, unsigned long long* p, size_t n) {
   hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, (int64_t)n, 0ull);
 }
@@ -486,7 +505,10 @@ sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
   ps.spin_limit = c->spin_limit;
   ps.gen_base = c->gen_base;
   c->gen_base += (uint32_t)n_rounds;
-  hipLaunchKernelGGL(k_rounds_persistent, dim3(ps.n_pairs + 2), dim3(kRoundThreads), 0, s, c->tb, c->w, ps);
+  if (c->tb.pol_split)
+    hipLaunchKernelGGL(k_rounds_persistent<true>, dim3(ps.n_pairs + 2), dim3(kRoundThreads), persist_dynamic_lds(c), s, c->tb, c->w, ps);
+  else
+    hipLaunchKernelGGL(k_rounds_persistent<false>, dim3(ps.n_pairs + 2), dim3(kRoundThreads), 0, s, c->tb, c->w, ps);
   return SP_OK;
 }
 
@@ -528,8 +550,9 @@ sp_status ensure_split_buffers(sp_ctx* c) {
   if ((s = dev_alloc(c, &w.win_pos, gcap * c->B)) != SP_OK) return s;
   if ((s = dev_alloc(c, &w.win_n, gcap)) != SP_OK) return s;
   w.gcap = (int32_t)gcap;
-  SP_HIP(c, hipHostMalloc((void**)&c->h_grp_n, sizeof(int32_t), hipHostMallocDefault));
-  *c->h_grp_n = A;
+  SP_HIP(c, hipHostMalloc((void**)&c->h_grp_n, 2 * sizeof(int32_t), hipHostMallocDefault));
+  c->h_grp_n[0] = A;
+  c->h_grp_n[1] = 1;
   SP_HIP(c, hipEventCreate(&c->ev_groups));
   return SP_OK;
 }
@@ -826,7 +849,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   }
   if (c->tb.pol_split) {
     // the rounds' launch grids depend on the number of groups
-    SP_HIP(c, hipMemcpyAsync(c->h_grp_n, w.grp_n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    SP_HIP(c, hipMemcpyAsync(c->h_grp_n, w.grp_n, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
     SP_HIP(c, hipEventRecord(c->ev_groups, s));
   }
   SP_HIP(c, hipGetLastError());
@@ -899,7 +922,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   if (tm) SP_HIP(c, hipEventRecord(c->ev[4], s));
   c->round_ms.clear();
   while (!c->done) {
-    const bool persist = c->persist && !c->tb.pol_split;     // the one-launch path iterates over applications
+    const bool persist = rounds_in_one_launch(c);
     int chunk = persist ? kPersistRounds : 64;
     if (max_rounds > 0) chunk = std::min(chunk, start + max_rounds - c->rounds_done);
     if (chunk <= 0) break;
@@ -1129,6 +1152,17 @@ sp_status sp_set_policy(sp_ctx* c, const sp_policy* p) {
     if (!g.ok) return SP_EDEVICE;
     sp_status s = ensure_split_buffers(c);
     if (s != SP_OK) return s;
+    // the resident rounds kernel with its per-wavefront windows: does the whole grid still fit?
+    c->persist_split = false;
+    if (c->persist) {
+      int cus = 0, per_cu = 0;
+      const size_t dyn = (size_t)(kRoundThreads / 64) * (size_t)c->B * (sizeof(float4) + sizeof(int32_t));
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess &&
+          hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_rounds_persistent<true>, kRoundThreads, dyn) == hipSuccess)
+        c->persist_split = (size_t)per_cu * (size_t)cus >= (size_t)c->ps.n_pairs + 2;
+      else
+        (void)hipGetLastError();
+    }
   }
   tb.pol_split = p->split_groups;
   return SP_OK;
@@ -1152,7 +1186,11 @@ sp_status sp_set_swap_cost(sp_ctx* c, int32_t app, const float* swap_ms_host) {
 
 int32_t sp_max_models(const sp_ctx* c) { return c ? c->Mmax : 0; }
 int32_t sp_max_classes(const sp_ctx* c) { return c ? c->Cmax : 0; }
-int32_t sp_rounds_in_one_launch(const sp_ctx* c) { return (c && c->persist && !c->tb.pol_split) ? 1 : 0; }
+int32_t sp_rounds_in_one_launch(const sp_ctx* c) {
+  if (!c) return 0;
+  DeviceGuard g(c->device);
+  return (g.ok && rounds_in_one_launch(const_cast<sp_ctx*>(c))) ? 1 : 0;
+}
 
 sp_status sp_debug_set_spin_limit(sp_ctx* c, int32_t polls) {
   if (!c || polls < 0) return SP_EINVAL;

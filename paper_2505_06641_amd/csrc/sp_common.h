@@ -93,7 +93,7 @@ struct Window {
   int32_t* sub_g;             // [n] subgroup code of the request at each grouped position: 0, or 1 + predicted class
   int32_t* grp_app;           // [gcap] application of each group
   int32_t* grp_end;           // [gcap] end of each group's range in service order
-  int32_t* grp_n;             // [1] number of groups
+  int32_t* grp_n;             // [2] number of groups; the most groups any application has
   int32_t* head;              // [2, gcap] first position that may still be live (double-buffered by round parity)
   int32_t* model;             // [n] outputs, indexed by request id
   int32_t* round_of;          // [n]

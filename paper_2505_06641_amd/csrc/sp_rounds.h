@@ -70,8 +70,7 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 template <int KIND>
 __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* ent, const float* lat, int nb, int B,
                                                                 double t, uint32_t cid0, float* cube_out, int only_b,
-                                                                int nthr) {
-  const int tid = threadIdx.x;
+                                                                int nthr, int tid) {
   const int sub = tid % kPairLanes, grp = tid / kPairLanes;
   const int n_pairs = (B + 1) / 2;
   unsigned long long best = 0ull;
@@ -123,14 +122,16 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
   return best;
 }
 
-// nthr: the threads taking part (a multiple of 64).  A score is summed by the same kPairLanes lanes in the
-// same order however many take part, so the result does not depend on it.
+// nthr: the threads taking part (a multiple of 64), numbered tid = 0 .. nthr - 1 (by default the first nthr
+// threads of the workgroup; a single wavefront passes its lane number).  A score is summed by the same
+// kPairLanes lanes in the same order however many take part, so the result does not depend on it.
 __device__ __forceinline__ unsigned long long triangle_best(int kind, const float4* ent, const float* lat, int nb, int B,
                                                            double t, uint32_t cid0, float* cube_out, int only_b,
-                                                           int nthr = kRoundThreads) {
-  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
-  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
-  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr);
+                                                           int nthr = kRoundThreads, int tid = -1) {
+  if (tid < 0) tid = threadIdx.x;
+  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
 }
 
 // Utility evaluations (terms key * EA * (1 - penalty)) behind the candidates of one (group, variant) pair

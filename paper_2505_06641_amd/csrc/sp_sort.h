@@ -152,7 +152,10 @@ __device__ __forceinline__ void segments_body(const SegArgs& g, const Window& w)
     w.grp_app[a] = a;
     w.grp_end[a] = seg[a + 1];
   }
-  if (threadIdx.x == 0) *w.grp_n = A;
+  if (threadIdx.x == 0) {
+    w.grp_n[0] = A;
+    w.grp_n[1] = 1;
+  }
   // prefixes of tiles and units over the applications: every thread takes a run of consecutive
   // applications, the runs' totals are scanned across the workgroup (launched with 256 threads)
   __shared__ int run_t[256], run_u[256];
@@ -490,7 +493,29 @@ __global__ __launch_bounds__(1024) void k_groups_compact(int n_slots, const int3
     if (tid == 0) base_s += total;
     __syncthreads();
   }
-  if (tid == 0) *w.grp_n = min(base_s, w.gcap);
+  const int G = min(base_s, w.gcap);
+  // the most groups any application has (the groups of an application are consecutive): it decides whether
+  // the resident rounds kernel, whose workgroups each serve all groups of one application, can take the window
+  __shared__ int max_run;
+  if (tid == 0) max_run = 0;
+  __threadfence();
+  __syncthreads();
+  for (int j = tid; j < G; j += 1024) {
+    const int a = w.grp_app[j];
+    if (j == 0 || w.grp_app[j - 1] != a) {
+      int lo = j, hi = G;                                 // first index past j whose application is not a
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (w.grp_app[mid] == a) lo = mid; else hi = mid;
+      }
+      atomicMax(&max_run, hi - j);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    w.grp_n[0] = G;
+    w.grp_n[1] = max_run;
+  }
 }
 
 // The four per-request outputs into the caller's arrays (any of them may be null), one launch.

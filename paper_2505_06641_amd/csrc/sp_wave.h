@@ -7,6 +7,13 @@
 
 namespace sp {
 
+// Orders this wavefront's LDS accesses around it (compiler fence; the hardware already runs one wavefront's
+// LDS operations in issue order).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // Inclusive prefix sum across a wavefront, or (ROWS_ONLY) inside each row of 16 lanes, with data-parallel
 // primitives: four shifts inside the rows, then the last lane of row 0/2 broadcast into row 1/3 and the
 // last lane of row 1 into rows 2 and 3.  No LDS traffic, one vector instruction per step.  Every lane of

@@ -460,11 +460,31 @@ def test_data_aware_group_splitting(gpu, head, name):
     ctx = binding.Context(w.profile, w.requests.n, policy=policy)
     x, app, D, wt = binding.to_device(w.requests)
     ctx.sp_score(x, app, D, wt)
-    assert not ctx.lib.sp_rounds_in_one_launch(ctx.h)
+    # sp_schedule above ran the rounds in one launch (a resident workgroup serves all groups of its application);
+    # one round per call below takes the two-kernel path: the two must agree decision for decision
+    assert ctx.lib.sp_rounds_in_one_launch(ctx.h)
     for rec in got["log"]:
         rc, dec = ctx.sp_greedy_round()
         assert rc == binding.SP_OK and dec == rec
     assert ctx.sp_greedy_round()[0] == binding.SP_DONE
+    ctx.close()
+
+
+def test_group_splitting_beyond_what_a_resident_workgroup_serves(gpu):
+    """More than 64 non-empty subgroups in one application: sp_schedule takes two kernels per round, with the
+    same parity; an application with few subgroups beside it changes nothing."""
+    torch, binding = gpu
+    w = wl.tiny(seed=101, n=4000, classes=(120, 3), models=(3, 2), max_batch=9, feat_dim=24, deadline=(6.0, 150.0),
+                fractions=(0.8, 0.2))
+    w.profile.W1[0] = (w.profile.W1[0] * 8.0).astype(np.float32)       # sharp head: most requests are confident
+    policy = wl.named_policy("sneakpeek")
+    policy.split_groups = 1
+    got, stats = full_parity(gpu, w, max_rounds=0, want_cube=True, policy=policy)
+    assert got["summary"]["done"] == 1 and stats["rounds"] > 10
+    ctx = binding.Context(w.profile, w.requests.n, policy=policy)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_score(x, app, D, wt)
+    assert not ctx.lib.sp_rounds_in_one_launch(ctx.h)
     ctx.close()
 
 
