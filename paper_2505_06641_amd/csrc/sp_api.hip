@@ -42,6 +42,7 @@ struct sp_ctx {
   int4* sort_desc = nullptr;         // [tiles_cap]
   uint32_t sort_gen = 0;             // generations handed out so far
   int32_t* seg1 = nullptr;           // [2] the one-segment plan of the pass over the application ids
+  float2* dw_g[2] = {nullptr, nullptr};   // [n] (deadline, weight) at each grouped position (two for two passes over the ids)
   State* h_state = nullptr;   // pinned mirror
   bool scored = false;
   int32_t n = 0;
@@ -335,6 +336,8 @@ sp_status build_ctx(sp_ctx* c, const sp_profile* p) {
   SP_HIP(c, hipMemset(c->sort_state, 0, (size_t)c->tiles_cap * 256 * sizeof(unsigned long long)));
   if ((s = dev_alloc(c, &c->sort_desc, (size_t)c->tiles_cap)) != SP_OK) return s;
   if ((s = dev_alloc(c, &c->seg1, 2)) != SP_OK) return s;
+  for (int i = 0; i < (app_passes(A) > 1 ? 2 : 1); ++i)
+    if ((s = dev_alloc(c, &c->dw_g[i], N)) != SP_OK) return s;
   SP_HIP(c, hipHostMalloc((void**)&c->h_state, sizeof(State), hipHostMallocDefault));
   std::memset(c->h_state, 0, sizeof(State));
   {
@@ -566,15 +569,15 @@ sp_status pack_mfma_blocks(sp_ctx* c, const sp_profile* p) {
 }
 
 template <typename T>
-void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, const int32_t* ids, const float* D,
-                          const float* wt, uint32_t* sortkey, float* logits) {
+void launch_score_generic(sp_ctx* c, hipStream_t s, int grid, const void* x, const int32_t* ids, const float2* dw,
+                          uint32_t* sortkey, float* logits) {
   const dim3 blk(kScoreWaves * kWave);
   if (c->Mmax <= 4)
-    hipLaunchKernelGGL((k_score_generic<T, 4>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+    hipLaunchKernelGGL((k_score_generic<T, 4>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, dw, sortkey, logits);
   else if (c->Mmax <= 8)
-    hipLaunchKernelGGL((k_score_generic<T, 8>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+    hipLaunchKernelGGL((k_score_generic<T, 8>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, dw, sortkey, logits);
   else
-    hipLaunchKernelGGL((k_score_generic<T, 16>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, D, wt, sortkey, logits);
+    hipLaunchKernelGGL((k_score_generic<T, 16>), dim3(grid), blk, c->score_lds, s, c->tb, c->w, (const T*)x, ids, dw, sortkey, logits);
 }
 
 int score_tile(const sp_ctx* c) { return (c->mfma_D > 0 || c->mlp_bf16) ? kMfTile : kScoreTile; }
@@ -595,13 +598,13 @@ sp_status static_scratch_for(sp_ctx* c, int device, unsigned char** out) {
 
 constexpr size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float* D, const float* wt,
-                  uint32_t* sortkey, float* logits) {
+void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, const float2* dw, uint32_t* sortkey,
+                  float* logits) {
   if (c->mlp_bf16) {
     const int grid = (c->n + kMfTile - 1) / kMfTile + c->A + kXcds;   // at least 8 * ceil(tiles / 8): see xcd_tile
 #define SP_LAUNCH_MLP(DUMP, SPLIT)                                                                                \
     hipLaunchKernelGGL((k_score_mlp_bf16<DUMP, SPLIT>), dim3(grid), dim3(kMfThreads), 0, s, c->tb, c->w,          \
-                       (const uint16_t*)x, ids, D, wt, sortkey, (const unsigned char*)c->w1p,                    \
+                       (const uint16_t*)x, ids, dw, sortkey, (const unsigned char*)c->w1p,                       \
                        (const int64_t*)c->w1_off, (const unsigned char*)c->blocks, (const int64_t*)c->block_off, \
                        (const float*)c->w_unscale, logits)
     if (logits) SP_LAUNCH_MLP(true, false);
@@ -617,15 +620,15 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
     do {                                                                                                          \
       if (logits)                                                                                                 \
         hipLaunchKernelGGL((k_score_logistic_split<DD, true, false>), dim3(grid), blk, 0, s, c->tb, c->w,         \
-                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const float*)x, ids, dw, sortkey, (const unsigned char*)c->blocks,                    \
                            (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
       else if (c->tb.pol_split)                                                                                   \
         hipLaunchKernelGGL((k_score_logistic_split<DD, false, true>), dim3(grid), blk, 0, s, c->tb, c->w,         \
-                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const float*)x, ids, dw, sortkey, (const unsigned char*)c->blocks,                    \
                            (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
       else                                                                                                        \
         hipLaunchKernelGGL((k_score_logistic_split<DD, false, false>), dim3(grid), blk, 0, s, c->tb, c->w,        \
-                           (const float*)x, ids, D, wt, sortkey, (const unsigned char*)c->blocks,                 \
+                           (const float*)x, ids, dw, sortkey, (const unsigned char*)c->blocks,                    \
                            (const int64_t*)c->block_off, (const float*)c->w_unscale, logits);                     \
     } while (0)
     if (c->mfma_D == 64) SP_LAUNCH_MF(64);
@@ -636,15 +639,15 @@ void launch_score(sp_ctx* c, hipStream_t s, const void* x, const int32_t* ids, c
   }
   const int grid = (c->n + kScoreTile - 1) / kScoreTile + c->A;
   if (c->dtype == SP_BF16)
-    launch_score_generic<uint16_t>(c, s, grid, x, ids, D, wt, sortkey, logits);
+    launch_score_generic<uint16_t>(c, s, grid, x, ids, dw, sortkey, logits);
   else
-    launch_score_generic<float>(c, s, grid, x, ids, D, wt, sortkey, logits);
+    launch_score_generic<float>(c, s, grid, x, ids, dw, sortkey, logits);
 }
 
 // One stable radix pass over the tiles of `plan`; (keys, vals) -> (keys_out, vals_out).
 void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int tiles, const uint32_t* keys, const int32_t* vals,
                 int shift, int clamp_a, const uint32_t* dtot_pass, uint32_t* keys_out, int32_t* vals_out,
-                const SegArgs* fused_segments = nullptr) {
+                const SegArgs* fused_segments = nullptr, const SortCarry* carry = nullptr) {
   if (c->sort_gen == 0xFFFFFFFFu) {                       // generation numbers about to wrap: start over
     hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((c->tiles_cap * 256 + 255) / 256)), dim3(256), 0, s, c->sort_state,
                        (int64_t)c->tiles_cap * 256, 0ull);
@@ -653,8 +656,13 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int tiles, const
   const uint32_t gen = ++c->sort_gen;
   SegArgs sg{};                                            // seg == null: no segment bookkeeping in this launch
   if (fused_segments) sg = *fused_segments;
-  hipLaunchKernelGGL(k_radix_pass, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals, shift,
-                     clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w);
+  if (carry)
+    hipLaunchKernelGGL(k_radix_pass<true>, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals,
+                       shift, clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w, *carry);
+  else
+    hipLaunchKernelGGL(k_radix_pass<false>, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals,
+                       shift, clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w,
+                       SortCarry{});
 }
 
 // Number of groups of the scored window: the applications, or the non-empty (application, subgroup) pairs.
@@ -779,9 +787,12 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     const uint32_t* kin = (const uint32_t*)app_dev;
     const int32_t* vin = nullptr;
     for (int p = 0; p < n_app_passes; ++p) {
-      // a single pass: the segment bookkeeping (which needs only the ids' digit totals) rides along
+      // a single pass: the segment bookkeeping (which needs only the ids' digit totals) rides along;
+      // every request's deadline and weight travel with it to its grouped position
+      const SortCarry cy = p == 0 ? SortCarry{deadline_ms_dev, weight_dev, nullptr, c->dw_g[n_app_passes - 1 - p]}
+                                  : SortCarry{nullptr, nullptr, c->dw_g[n_app_passes - p], c->dw_g[n_app_passes - 1 - p]};
       radix_pass(c, s, whole, tiles1, kin, vin, 8 * p, p == 0 ? A : 0, c->dtot_app + 256 * p, altK, altV,
-                 n_app_passes == 1 ? &seg_args : nullptr);
+                 n_app_passes == 1 ? &seg_args : nullptr, &cy);
       std::swap(curK, altK);
       std::swap(curV, altV);
       kin = curK;
@@ -798,7 +809,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     // posterior -> EA -> key, one pass over the features
     uint32_t* sortkey = altK;
     if (tm) SP_HIP(c, hipEventRecord(c->ev[1], s));
-    launch_score(c, s, x_dev, curV, deadline_ms_dev, weight_dev, sortkey, nullptr);
+    launch_score(c, s, x_dev, curV, c->dw_g[0], sortkey, nullptr);
     if (tm) SP_HIP(c, hipEventRecord(c->ev[2], s));
     // service order: inside each application by (key descending, id ascending).  The passes carry
     // positions of the grouped array (identity to start with), the grouped ids stay where they are.
@@ -1014,7 +1025,7 @@ sp_status sp_debug_dump(sp_ctx* c, int32_t kind, void* stream, const void* x_dev
       const int64_t cnt = (int64_t)n * c->Cmax;
       hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, (float*)dst_dev, cnt, 0.0f);
       // same kernel as the scoring pass, with the EA / key epilogue switched off
-      launch_score(c, s, x_dev, c->w.id_s, nullptr, nullptr, nullptr, (float*)dst_dev);
+      launch_score(c, s, x_dev, c->w.id_s, nullptr, nullptr, (float*)dst_dev);
       break;
     }
     default:

@@ -40,8 +40,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 // Called by one lane per request.
 template <int MT>
 __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w, int a, int pos, int id, int M,
-                                               const float (&ea_raw)[MT], const float* D, const float* wt,
-                                               uint32_t* sortkey, int sub) {
+                                               const float (&ea_raw)[MT], const float2* dw_g, uint32_t* sortkey,
+                                               int sub) {
   if (tb.pol_split) w.sub_g[pos] = sub;
   // with a prior (Sec. 4.2 eq. (10)-(11)) the posterior is (alpha + k theta) / (sum alpha + k), and
   // eq. (9) on it is an affine map of eq. (9) on theta; gain 1 and bias 0 leave the value untouched
@@ -60,7 +60,8 @@ __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w
     var += (m < M) ? dv * dv : 0.f;
   }
   var /= (float)M;
-  float Di = D[id], wi = wt[id];
+  const float2 dw = dw_g[pos];            // (deadline, weight), brought to the grouped position by the grouping pass
+  float Di = dw.x, wi = dw.y;
   uint32_t err = 0;
   if (!(Di > 0.f)) err |= kErrDeadline;
   if (!(wi >= 0.f)) err |= kErrWeight;
@@ -80,8 +81,8 @@ __device__ __forceinline__ void finish_request(const Tables& tb, const Window& w
 
 template <typename T, int MT>
 __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
-    Tables tb, Window w, const T* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ D,
-    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, float* __restrict__ logits_out) {
+    Tables tb, Window w, const T* __restrict__ x, const int32_t* __restrict__ ids, const float2* __restrict__ dw_g,
+    uint32_t* __restrict__ sortkey, float* __restrict__ logits_out) {
   constexpr int RW = kScoreRW;
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void k_score_generic(
     for (int o = 32; o > 0; o >>= 1) cls = min(cls, __shfl_xor(cls, o));
     const int sub = (1.0f / st > 0.5f) ? 1 + cls : 0;
     if (lane == 0 && r < nr && logits_out == nullptr)
-      finish_request<MT>(tb, w, a, p0 + r, ids[p0 + r], M, row, D, wt, sortkey, sub);
+      finish_request<MT>(tb, w, a, p0 + r, ids[p0 + r], M, row, dw_g, sortkey, sub);
   }
 }
 

@@ -46,8 +46,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const f32x4& v) { return __builtin_b
 
 template <bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
-    Tables tb, Window w, const uint16_t* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
-    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ w1p,
+    Tables tb, Window w, const uint16_t* __restrict__ x, const int32_t* __restrict__ ids, const float2* __restrict__ dw_g,
+    uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ w1p,
     const int64_t* __restrict__ w1_off /*[A] bytes*/, const unsigned char* __restrict__ blocks,
     const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
     float* __restrict__ logits_out) {
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     }
   }
 
-  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, dw_g,
                                   sortkey, logits_out);
 }
 

@@ -392,8 +392,8 @@ __device__ __forceinline__ void softmax_phase(const float4* blk, f32x16& acc, fl
 template <bool SPLIT>
 __device__ __forceinline__ void score_epilogue(const Tables& tb, const Window& w, const f32x16& eacc, float m2,
                                                float best_z, int best_c, int a, int M, int pos, int id, bool valid,
-                                               int r, int g, const float* __restrict__ Dl,
-                                               const float* __restrict__ wt, uint32_t* __restrict__ sortkey) {
+                                               int r, int g, const float2* __restrict__ dw_g,
+                                               uint32_t* __restrict__ sortkey) {
   // eacc[v] of lane (r, g) is table row 8*(v/4) + 4*g + v%4 for request r:
   // v 0..3 -> variants 4g..4g+3, v 4..7 -> variants 8+4g..8+4g+3, v = 8 at g = 0 -> the sum of exponentials
   const float ssum = __shfl(eacc[8], r);
@@ -436,7 +436,8 @@ __device__ __forceinline__ void score_epilogue(const Tables& tb, const Window& w
     if (g == 0) w.sub_g[pos] = (pmax * inv > 0.5f) ? 1 + cmax : 0;
   }
   if (g == 0) {
-    const float Di = Dl[id], wi = wt[id];
+    const float2 dw = dw_g[pos];           // (deadline, weight), brought to the grouped position by the grouping pass
+    const float Di = dw.x, wi = dw.y;
     uint32_t err = 0;
     if (!(Di > 0.f)) err |= kErrDeadline;
     if (!(wi >= 0.f)) err |= kErrWeight;
@@ -456,7 +457,7 @@ template <int D, bool DUMP, bool SPLIT>
 __device__ __forceinline__ void class_tiles_and_finish(
     const Tables& tb, const Window& w, float4* buf_a, float4* buf_b, float4* buf_c, const float4* __restrict__ src,
     const f16x8 (&xh)[D / 16], const f16x8 (&xl)[D / 16], float unscale, int a, int CT, int C, int M, int pos, int id,
-    bool valid, const float* __restrict__ Dl, const float* __restrict__ wt, uint32_t* __restrict__ sortkey,
+    bool valid, const float2* __restrict__ dw_g, uint32_t* __restrict__ sortkey,
     float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -539,7 +540,7 @@ __device__ __forceinline__ void class_tiles_and_finish(
 #pragma unroll
     for (int v = 9; v < 16; ++v) eacc[v] = 0.f;
   }
-  score_epilogue<SPLIT>(tb, w, eacc, m2, best_z, best_c, a, M, pos, id, valid, r, g, Dl, wt, sortkey);
+  score_epilogue<SPLIT>(tb, w, eacc, m2, best_z, best_c, a, M, pos, id, valid, r, g, dw_g, sortkey);
 }
 
 // This lane's half of its request's features, k = g*D/2 + [0, D/2): the row scaled by a power of two into
@@ -565,7 +566,12 @@ __device__ __forceinline__ float load_split_features(const float* __restrict__ x
         for (int i = 0; i < 8; ++i) {
           const int rid = __shfl(id, 8 * ps + i);
           dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (4 * lane < d) dst[i] = *reinterpret_cast<const float4*>(x + (int64_t)rid * d + 4 * lane);
+          // feature rows are read once: a streaming load, so that they do not push the packed blocks,
+          // which every workgroup of the die reads again, out of its L2
+          if (4 * lane < d) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + (int64_t)rid * d + 4 * lane));
+            dst[i] = make_float4(v[0], v[1], v[2], v[3]);
+          }
         }
       };
       fetch_rows(0, rows[0]);
@@ -632,8 +638,8 @@ __device__ __forceinline__ int xcd_tile(int wg, int n_tiles) {
 
 template <int D, bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
-    Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ Dl,
-    const float* __restrict__ wt, uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
+    Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float2* __restrict__ dw_g,
+    uint32_t* __restrict__ sortkey, const unsigned char* __restrict__ blocks,
     const int64_t* __restrict__ block_off /*[A] bytes*/, const float* __restrict__ w_unscale /*[A]*/,
     float* __restrict__ logits_out) {
   using SB = SplitBlock<D>;
@@ -660,7 +666,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
   f16x8 xh[D / 16], xl[D / 16];
   float4* scratch = (wave < kMfWaves / 2 ? buf_b : buf_c) + (wave % (kMfWaves / 2)) * (8 * 66);
   const float unscale = load_split_features<D>(x, id, d, scratch, lane, w_unscale[a], xh, xl);
-  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, Dl, wt,
+  class_tiles_and_finish<D, DUMP, SPLIT>(tb, w, buf_a, buf_b, buf_c, src, xh, xl, unscale, a, CT, C, M, pos, id, valid, dw_g,
                                   sortkey, logits_out);
 }
 

@@ -297,13 +297,25 @@ __device__ __forceinline__ uint32_t scan256_excl(uint32_t v, uint32_t* wave_tot 
   return before + incl - v;
 }
 
+// Two floats that travel with an element through a pass (the grouping pass brings every request's deadline
+// and weight to its grouped position, so that the scoring kernel reads them in order instead of gathering
+// them by request id, 4 useful bytes per 64-byte line): read from two arrays or from one array of pairs,
+// indexed by element, written as pairs.
+struct SortCarry {
+  const float* in0;            // [n], with in1; or null
+  const float* in1;
+  const float2* in01;          // [n] pairs (a second pass); or null
+  float2* out;                 // [n] pairs at the elements' new positions
+};
+
 // One stable pass: (keys_in, vals_in) -> (keys_out, vals_out) by the digit at `shift`.  vals_in == nullptr
 // means the identity (value = element index).  dtot_pass: this pass's slab of digit totals.  state:
 // [tiles][256] published words; gen: this launch's generation (never reused while the array lives).
+template <bool CARRY>
 __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
     SortPlan sp, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int shift, int clamp_a,
     const uint32_t* __restrict__ dtot_pass, unsigned long long* __restrict__ state, uint32_t gen, int spin_limit,
-    uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out, State* st, SegArgs sg, Window sw) {
+    uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out, State* st, SegArgs sg, Window sw, SortCarry cy) {
   // One extra workgroup (sg.seg != null) does k_segments' job beside the pass over the application ids,
   // which needs nothing but the ids' digit totals: a launch and its trips to memory less per window.
   if (sg.seg != nullptr && (int)blockIdx.x == (int)gridDim.x - 1) {
@@ -316,6 +328,7 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
   __shared__ uint32_t wave_tot[kSortWaves];
   __shared__ uint32_t skey[kSortTile];
   __shared__ int32_t sval[kSortTile];
+  __shared__ float2 spay[CARRY ? kSortTile : 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int s, beg, end, first;
   if (!sort_tile(sp, blockIdx.x, s, beg, end, first)) return;
@@ -330,6 +343,15 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
     const int i = beg + (wave * kSortItems + c) * 64 + lane;
     key[c] = i < end ? sort_key_at(keys_in, i, clamp_a, bad) : 0u;
     val[c] = i < end ? (vals_in ? vals_in[i] : i) : 0;
+  }
+  float2 pay[CARRY ? kSortItems : 1];
+  if (CARRY) {
+#pragma unroll
+    for (int c = 0; c < kSortItems; ++c) {
+      const int i = beg + (wave * kSortItems + c) * 64 + lane;
+      pay[c] = make_float2(0.f, 0.f);
+      if (i < end) pay[c] = cy.in01 ? cy.in01[i] : make_float2(cy.in0[i], cy.in1[i]);
+    }
   }
   if (bad) atomicOr(&st->err, kErrApp);
   __syncthreads();
@@ -414,6 +436,7 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
       const uint32_t p = lstart[dg] + cnt[wave][dg] + rank[c];
       skey[p] = key[c];
       sval[p] = val[c];
+      if (CARRY) spay[p] = pay[c];
     }
   }
   __syncthreads();
@@ -424,6 +447,7 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
     const uint32_t dst = dbase[(k >> shift) & 255u] + (uint32_t)j;
     keys_out[dst] = k;
     vals_out[dst] = sval[j];
+    if (CARRY) cy.out[dst] = spay[j];
   }
 }
 
