@@ -305,6 +305,14 @@ def main():
         stream("copy_outputs", 32 * N, c_ms, "four per-request outputs read and written"),
     ]
     out["hbm_copy_measured_gbs"] = binding.sp_debug_copy_rate(1 << 28)
+    # the whole step against the scoring kernel's ceilings: its algorithmic flops and the algorithmic bytes of
+    # every stage over the step's wall time (the rounds work on LDS-resident windows: no bytes counted for them)
+    step_bytes = k_bytes + (16 + 68 + 57 + 32) * N
+    out["whole_step_roofline"] = {"algorithmic_flops": flops, "algorithmic_bytes": step_bytes,
+                                  "tflops": flops / (ms_per_step * 1e-3) / 1e12,
+                                  "frac_of_scoring_kernel_ceiling": flops / (ms_per_step * 1e-3) / 1e12 / peak_c,
+                                  "gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                                  "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS}
     if not args.no_cpu_baseline:
         default_sample = {"cfg1": n, "cfg2": n, "cfg3": n, "cfg4": 65536, "cfg5": 1048576}[args.workload]
         ns = min(n, args.cpu_sample or default_sample)

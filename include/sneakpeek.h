@@ -335,6 +335,16 @@ sp_status sp_debug_set_generation(sp_ctx* ctx, uint32_t generation);
 sp_status sp_debug_set_spin_limit(sp_ctx* ctx, int32_t polls);
 
 /*
+ * Test hook, not on the hot path (implements nothing of the paper).  A tile of a radix pass of the ordering
+ * learns the digit counts of the tiles before it in its segment by polling words they publish; the polling
+ * is bounded, and a look-back that runs out raises an error that the next sp_greedy_round / sp_schedule
+ * reports as SP_EDEVICE (the window has to be scored again; the context stays usable).  polls > 0 sets the
+ * bound, polls < 0 makes every look-back give up at once (a test's way into that path with every kernel
+ * still ending normally), 0 restores the default (2^20).  SP_EINVAL: ctx NULL.
+ */
+sp_status sp_debug_set_sort_spin_limit(sp_ctx* ctx, int32_t polls);
+
+/*
  * Diagnostic, not on the hot path and no part of the paper's method: the rate at which the device's matrix
  * cores run the half-precision instruction the scoring kernel is built on when nothing else competes.
  * random_bits = 0: constant operands; 1: operands with random bits.  idle in {0, 1, 2, 4, 8}: after every

@@ -21,7 +21,7 @@ SP_DUMP_ORDER, SP_DUMP_SEGMENTS, SP_DUMP_SCORE_CUBE, SP_DUMP_LOGITS = 0, 1, 2, 3
 
 EXPORTS = ["sp_create", "sp_destroy", "sp_score", "sp_greedy_round", "sp_greedy_round_static", "sp_schedule", "sp_debug_dump",
            "sp_strerror", "sp_last_hip_error", "sp_max_models", "sp_max_classes",
-           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_copy_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
+           "sp_rounds_in_one_launch", "sp_debug_mfma_rate", "sp_debug_copy_rate", "sp_debug_set_generation", "sp_debug_set_spin_limit", "sp_debug_set_sort_spin_limit", "sp_set_prior", "sp_set_swap_cost", "sp_set_policy",
            "sp_set_timing", "sp_get_timing", "sp_get_round_times"]
 
 
@@ -118,6 +118,8 @@ def load_library(path: Optional[str] = None):
     lib.sp_debug_set_generation.restype = C.c_int
     lib.sp_debug_set_spin_limit.argtypes = [vp, C.c_int32]
     lib.sp_debug_set_spin_limit.restype = C.c_int
+    lib.sp_debug_set_sort_spin_limit.argtypes = [vp, C.c_int32]
+    lib.sp_debug_set_sort_spin_limit.restype = C.c_int
     lib.sp_debug_mfma_rate.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.sp_debug_mfma_rate.restype = C.c_int
     lib.sp_debug_copy_rate.argtypes = [C.c_int, C.c_int64, vp, C.POINTER(C.c_double)]
@@ -317,6 +319,9 @@ class Context:
 
     def sp_debug_set_spin_limit(self, polls):
         return self._check(self.lib.sp_debug_set_spin_limit(self.h, int(polls)), "sp_debug_set_spin_limit")
+
+    def sp_debug_set_sort_spin_limit(self, polls):
+        return self._check(self.lib.sp_debug_set_sort_spin_limit(self.h, int(polls)), "sp_debug_set_sort_spin_limit")
 
     def sp_debug_set_generation(self, generation):
         return self._check(self.lib.sp_debug_set_generation(self.h, int(generation)), "sp_debug_set_generation")

@@ -62,6 +62,7 @@ struct sp_ctx {
   Persist ps{};
   uint32_t gen_base = 0;             // slot generations handed out so far
   int32_t spin_limit = kSpinLimit;   // polls before a wait between resident workgroups is given up
+  int32_t sort_spin_limit = kSortSpinLimit;   // polls before a radix pass's look-back is given up (< 0: at once)
   long long* h_ticks = nullptr;      // pinned mirror of ps.ticks
   double tick_ms = 0.0;              // milliseconds per timestamp tick
   std::vector<float> round_ms;       // per-round latencies of the last timed sp_schedule on that path
@@ -658,10 +659,10 @@ void radix_pass(sp_ctx* c, hipStream_t s, const SortPlan& plan, int tiles, const
   if (fused_segments) sg = *fused_segments;
   if (carry)
     hipLaunchKernelGGL(k_radix_pass<true>, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals,
-                       shift, clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w, *carry);
+                       shift, clamp_a, dtot_pass, c->sort_state, gen, c->sort_spin_limit, keys_out, vals_out, c->w.st, sg, c->w, *carry);
   else
     hipLaunchKernelGGL(k_radix_pass<false>, dim3(tiles + (fused_segments ? 1 : 0)), dim3(kSortThreads), 0, s, plan, keys, vals,
-                       shift, clamp_a, dtot_pass, c->sort_state, gen, kSortSpinLimit, keys_out, vals_out, c->w.st, sg, c->w,
+                       shift, clamp_a, dtot_pass, c->sort_state, gen, c->sort_spin_limit, keys_out, vals_out, c->w.st, sg, c->w,
                        SortCarry{});
 }
 
@@ -1206,6 +1207,12 @@ int32_t sp_rounds_in_one_launch(const sp_ctx* c) {
 sp_status sp_debug_set_spin_limit(sp_ctx* c, int32_t polls) {
   if (!c || polls < 0) return SP_EINVAL;
   c->spin_limit = polls == 0 ? kSpinLimit : polls;
+  return SP_OK;
+}
+
+sp_status sp_debug_set_sort_spin_limit(sp_ctx* c, int32_t polls) {
+  if (!c) return SP_EINVAL;
+  c->sort_spin_limit = polls == 0 ? kSortSpinLimit : polls;
   return SP_OK;
 }
 

@@ -404,7 +404,8 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
         for (int q = 0; q < kLookBack; ++q) {
           if (t2 - q < first || found || lost) continue;
           unsigned long long w = v[q];
-          for (int k = 0; (uint32_t)(w >> 32) != gen; ++k) {          // not published yet: poll this one
+          if (spin_limit < 0) lost = true;                             // a test's way into the failure path: give up unseen
+          for (int k = 0; !lost && (uint32_t)(w >> 32) != gen; ++k) {  // not published yet: poll this one
             if (k >= spin_limit) { lost = true; break; }
             __builtin_amdgcn_s_sleep(1);
             w = __hip_atomic_load(state + (size_t)(t2 - q) * 256 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -890,6 +890,32 @@ def test_a_wait_that_runs_out_fails_the_call_and_the_context_carries_on_with_two
     ref["close"]()
 
 
+def test_a_look_back_that_runs_out_fails_the_window_and_the_context_carries_on(gpu):
+    """The bounded look-back of the radix passes, forced to give up from the host (every kernel still ends
+    normally): the rounds report SP_EDEVICE, the window has to be scored again, and then all is as before."""
+    torch, binding = gpu
+    # one application with three sort tiles, one with a single tile (which never looks back)
+    w = wl.tiny(seed=7955, n=12000, classes=(9, 5), models=(3, 2), max_batch=8, feat_dim=12, deadline=(4.0, 90.0),
+                fractions=(0.85, 0.15))
+    ref = run_window(gpu, w, 0)
+    ctx = binding.Context(w.profile, 12000)
+    x, app, D, wt = binding.to_device(w.requests)
+    ctx.sp_debug_set_sort_spin_limit(-1)
+    ctx.sp_score(x, app, D, wt)
+    for call in (ctx.sp_greedy_round, lambda: ctx.sp_schedule(0, log_capacity=16)):
+        with pytest.raises(binding.SneakPeekError) as e:
+            call()
+        assert e.value.status in (binding.SP_EDEVICE, binding.SP_ESTATE)
+    assert b"look-back" in ctx.lib.sp_last_hip_error(ctx.h)
+    ctx.sp_debug_set_sort_spin_limit(0)
+    got = run_window(gpu, w, 0, ctx=ctx)
+    assert got["log"] == ref["log"] and got["summary"] == ref["summary"]
+    for k in ("model", "round_of", "order_of", "util", "order"):
+        assert np.array_equal(got[k], ref[k]), k
+    ctx.close()
+    ref["close"]()
+
+
 @pytest.mark.parametrize("path", ["one launch", "two kernels"])
 def test_timing_aid_changes_nothing_and_reports_sane_times(gpu, path):
     """sp_set_timing: the same schedule with stage and per-round timing on, on both rounds paths; the
