@@ -775,8 +775,12 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   const int tiles2 = n / kSortTile + A;                       // upper bound on the tiles inside the applications' ranges
   const int64_t slab = c->tiles_cap * 256;                    // words per pass of dtot_key
   // a single pass over the application ids: every application's count is one of its digit totals
-  SegArgs seg_args{n, A, nullptr, c->dtot_app, score_tile(c), kSortTile, w.seg, w.tile_start, w.unit_start, w.tile_desc,
-                   c->sort_desc};
+  // Applications whose whole range fits one workgroup's LDS are ordered by one kernel (k_sort_small) and get
+  // no tiles in the passes; not with subgroups (their passes over the labels need the tiles) and not with more
+  // applications than that kernel is worth a workgroup each.
+  const int small_cap = (!c->tb.pol_split && A <= 1024) ? kSmallSortCap : 0;
+  SegArgs seg_args{n, A, nullptr, c->dtot_app, score_tile(c), kSortTile, small_cap, w.seg, w.tile_start, w.unit_start,
+                   w.tile_desc, c->sort_desc};
   if (n > 0) {
     // requests grouped by application: stable pass(es) over the application id, read straight from the
     // caller's array (ids outside [0, A) become A and raise the error flag)
@@ -815,17 +819,24 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
     // service order: inside each application by (key descending, id ascending).  The passes carry
     // positions of the grouped array (identity to start with), the grouped ids stay where they are.
     SortPlan per_app{w.seg, w.unit_start, A, c->sort_desc};
-    hipLaunchKernelGGL(k_digit_totals, dim3(tiles2), dim3(kSortThreads), 0, s, per_app, (const uint32_t*)sortkey, 0, 0, 4,
-                       c->tiles_cap, c->dtot_key, (uint32_t*)nullptr, 0, (int64_t)0, (int64_t)0, w.st);
+    // with n <= small_cap every application is small: the tiled passes have nothing to do and are not launched
+    const bool tiled = !(small_cap > 0 && n <= small_cap);
+    if (tiled)
+      hipLaunchKernelGGL(k_digit_totals, dim3(tiles2), dim3(kSortThreads), 0, s, per_app, (const uint32_t*)sortkey, 0, 0, 4,
+                         c->tiles_cap, c->dtot_key, (uint32_t*)nullptr, 0, (int64_t)0, (int64_t)0, w.st);
     uint32_t *k_in = sortkey, *k_out = curK;
     const int32_t* v_in = nullptr;
     int32_t *v_out = altV, *v_spare = c->bufV[2];
     for (int p = 0; p < 4; ++p) {
-      radix_pass(c, s, per_app, tiles2, k_in, v_in, 8 * p, 0, c->dtot_key + slab * p, k_out, v_out);
+      if (tiled) radix_pass(c, s, per_app, tiles2, k_in, v_in, 8 * p, 0, c->dtot_key + slab * p, k_out, v_out);
       std::swap(k_in, k_out);
       v_in = v_out;
       std::swap(v_out, v_spare);
     }
+    // the small applications, straight into the arrays the fourth pass has written (or would have)
+    if (small_cap > 0)
+      hipLaunchKernelGGL(k_sort_small, dim3(A), dim3(kSmallSortThreads), 0, s, (const int32_t*)w.seg, (const uint32_t*)sortkey,
+                         k_in, const_cast<int32_t*>(v_in));
     if (c->tb.pol_split) {
       // subgroups: further stable passes over the subgroup codes make the order (subgroup, key) inside
       // every application; then the non-empty (application, subgroup) pairs become the rounds' groups

@@ -110,6 +110,7 @@ struct SegArgs {
   const uint32_t* sorted_app;   // application-sorted keys (used when digit_tot is null)
   const uint32_t* digit_tot;    // or: the count of every application id (one radix pass over the ids)
   int32_t tile, unit;           // requests per scoring tile and per sort tile
+  int32_t small_cap;            // applications with at most this many requests get no sort tiles (k_sort_small orders them); 0: none
   int32_t* seg;
   int32_t* tile_start;
   int32_t* unit_start;
@@ -167,7 +168,7 @@ __device__ __forceinline__ void segments_body(const SegArgs& g, const Window& w)
   for (int a = a_lo; a < a_hi; ++a) {
     const int na = seg[a + 1] - seg[a];
     ts += (na + tile - 1) / tile;
-    us += (na + unit - 1) / unit;
+    us += na > g.small_cap ? (na + unit - 1) / unit : 0;
   }
   if (on) {
     run_t[tid] = ts;
@@ -198,7 +199,7 @@ __device__ __forceinline__ void segments_body(const SegArgs& g, const Window& w)
       s_seg[a] = sb;
     }
     ts += (na + tile - 1) / tile;
-    us += (na + unit - 1) / unit;
+    us += na > g.small_cap ? (na + unit - 1) / unit : 0;
   }
   if (on && tid == 255) {
     tile_start[A] = run_t[255];
@@ -237,7 +238,7 @@ __device__ __forceinline__ void segments_body(const SegArgs& g, const Window& w)
     ts = ts0;
     us = us0;
     for (int a = a_lo; a < a_hi; ++a) {
-      const int sb = seg[a], se = seg[a + 1], nt = (se - sb + tile - 1) / tile, nu = (se - sb + unit - 1) / unit;
+      const int sb = seg[a], se = seg[a + 1], nt = (se - sb + tile - 1) / tile, nu = se - sb > g.small_cap ? (se - sb + unit - 1) / unit : 0;
       for (int t = 0; t < nt; ++t) tile_desc[ts + t] = make_int4(a, sb + t * tile, se, 0);
       for (int u = 0; u < nu; ++u) sort_desc[us + u] = make_int4(a, sb + u * unit, min(sb + (u + 1) * unit, se), us);
       ts += nt;
@@ -284,16 +285,17 @@ __global__ __launch_bounds__(kSortThreads) void k_digit_totals(SortPlan sp, cons
   }
 }
 
-// Exclusive prefix sums of one value per thread over the first 256 threads of the workgroup (all
-// kSortThreads threads call it; those beyond 255 pass 0 and get the total).
-__device__ __forceinline__ uint32_t scan256_excl(uint32_t v, uint32_t* wave_tot /*[kSortWaves]*/) {
+// Exclusive prefix sums of one value per thread over the first 256 threads of the workgroup (all of its
+// threads call it; those beyond 255 pass 0 and get the total).
+template <int WAVES = kSortWaves>
+__device__ __forceinline__ uint32_t scan256_excl(uint32_t v, uint32_t* wave_tot /*[WAVES]*/) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t incl = wave_scan_incl(v);
   __syncthreads();
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
   uint32_t before = 0;
-  for (int i = 0; i < kSortWaves; ++i) before += i < wave ? wave_tot[i] : 0u;
+  for (int i = 0; i < WAVES; ++i) before += i < wave ? wave_tot[i] : 0u;
   return before + incl - v;
 }
 
@@ -449,6 +451,101 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_pass(
     keys_out[dst] = k;
     vals_out[dst] = sval[j];
     if (CARRY) cy.out[dst] = spay[j];
+  }
+}
+
+// All four key passes of one application in one kernel, for applications whose whole range fits one
+// workgroup's LDS (at most kSmallSortCap requests; k_segments gives such applications no tiles in the passes
+// above).  A window of a few thousand requests is otherwise six dependent launches of a few microseconds each.
+// The elements live in registers between the passes (wavefront w holds elements [1024 w, 1024 (w + 1)) in
+// order, 64 per chunk); a pass ranks them like k_radix_pass, scans the counts over the wavefronts and the
+// digits, places the (key, value) pairs in LDS in sorted order and reads them back.  Values are grouped
+// positions, as in the passes above; the result goes to the same arrays the last of those passes writes.
+constexpr int kSmallSortThreads = 1024;
+constexpr int kSmallSortWaves = kSmallSortThreads / kWave;
+constexpr int kSmallSortItems = 16;
+constexpr int kSmallSortCap = kSmallSortThreads * kSmallSortItems;   // 16,384
+
+__global__ __launch_bounds__(kSmallSortThreads) void k_sort_small(const int32_t* __restrict__ seg,
+                                                                  const uint32_t* keys_in /* may be keys_out */,
+                                                                  uint32_t* keys_out, int32_t* __restrict__ vals_out) {
+  __shared__ unsigned long long buf[kSmallSortCap];            // key << 32 | value, in sorted order
+  __shared__ uint32_t cnt[kSmallSortWaves][256];
+  __shared__ uint32_t lstart[256];
+  __shared__ uint32_t wave_tot[kSmallSortWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b0 = seg[blockIdx.x], n = seg[blockIdx.x + 1] - b0;
+  if (n <= 0 || n > kSmallSortCap) return;                     // (uniform) empty, or sorted by the tiled passes
+  // wavefronts and chunks that hold elements (the ranking is the expensive part: nothing is spent on empty ones)
+  const int n_waves = (n + kSmallSortItems * 64 - 1) / (kSmallSortItems * 64);
+  const int my_chunks = min(kSmallSortItems, max(0, (n - wave * kSmallSortItems * 64 + 63) / 64));
+  uint32_t key[kSmallSortItems];
+  int32_t val[kSmallSortItems];
+#pragma unroll
+  for (int c = 0; c < kSmallSortItems; ++c) {
+    const int e = (wave * kSmallSortItems + c) * 64 + lane;
+    key[c] = e < n ? keys_in[b0 + e] : 0u;
+    val[c] = b0 + e;
+  }
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int shift = 0; shift < 32; shift += 8) {
+    for (int i = tid; i < n_waves * 256; i += kSmallSortThreads) cnt[0][i] = 0u;
+    __syncthreads();
+    uint32_t rank[kSmallSortItems];
+#pragma unroll
+    for (int c = 0; c < kSmallSortItems; ++c) {
+      rank[c] = 0;
+      if (c < my_chunks) {                                       // uniform over the wavefront
+        const int e = (wave * kSmallSortItems + c) * 64 + lane;
+        const bool valid = e < n;
+        const uint32_t dg = (key[c] >> shift) & 255u;
+        const unsigned long long same = match_digit(dg, valid);
+        const int leader = valid ? (__ffsll((long long)same) - 1) : lane;
+        uint32_t before = 0;
+        if (valid && lane == leader) before = atomicAdd(&cnt[wave][dg], (uint32_t)__popcll(same));
+        before = __shfl(before, leader);
+        rank[c] = before + (uint32_t)__popcll(same & lt);
+      }
+    }
+    __syncthreads();
+    uint32_t mine = 0;
+    if (tid < 256) {
+      for (int w = 0; w < n_waves; ++w) {
+        const uint32_t c = cnt[w][tid];
+        cnt[w][tid] = mine;
+        mine += c;
+      }
+    }
+    const uint32_t ls = scan256_excl<kSmallSortWaves>(mine, wave_tot);
+    if (tid < 256) lstart[tid] = ls;
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kSmallSortItems; ++c) {
+      const int e = (wave * kSmallSortItems + c) * 64 + lane;
+      if (e < n) {
+        const uint32_t dg = (key[c] >> shift) & 255u;
+        buf[lstart[dg] + cnt[wave][dg] + rank[c]] = ((unsigned long long)key[c] << 32) | (unsigned long long)(uint32_t)val[c];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kSmallSortItems; ++c) {
+      const int e = (wave * kSmallSortItems + c) * 64 + lane;
+      if (e < n) {
+        const unsigned long long kv = buf[e];
+        key[c] = (uint32_t)(kv >> 32);
+        val[c] = (int32_t)(uint32_t)kv;
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int c = 0; c < kSmallSortItems; ++c) {
+    const int e = (wave * kSmallSortItems + c) * 64 + lane;
+    if (e < n) {
+      keys_out[b0 + e] = key[c];
+      vals_out[b0 + e] = val[c];
+    }
   }
 }
 
