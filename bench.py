@@ -133,7 +133,7 @@ def main():
                          "the known-size kernel that hardware byte counters of a profiler run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path would shard by application); "
+        print("bench.py: this library runs on one GPU only (the path would shard by application); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -506,6 +506,7 @@ sp_status launch_rounds_persistent(sp_ctx* c, hipStream_t s, int n_rounds) {
     c->gen_base = 0;
   }
   ps.n_rounds = n_rounds;
+  ps.all_to_all = ps.n_pairs <= kAllToAllPairs ? 1 : 0;
   ps.spin_limit = c->spin_limit;
   ps.gen_base = c->gen_base;
   c->gen_base += (uint32_t)n_rounds;

@@ -13,7 +13,11 @@
 //     requests.  Every position of the service order is visited once per launch, not once per round;
 //   * the arg max over all pairs goes through one slot per pair and a reducing workgroup: every pair
 //     publishes its best candidate, the reducer polls the slots (one per thread), takes the maximum and
-//     publishes the decision, which one thread of every pair polls.  Slots and the decision are pairs of
+//     publishes the decision, which one thread of every pair polls.  With few pairs (kAllToAllPairs) there
+//     is no reducer: every pair polls all slots itself and takes the maximum, which halves the trips
+//     through the fabric between a round's last candidate and its decision (the decisions are the same:
+//     every pair applies the reducer's rule to the same words; pair 0 passes the decision on to the commit
+//     workgroup).  Slots and the decision are pairs of
 //     64-bit words, each carrying the generation number of the round it belongs to, written and polled
 //     with relaxed device-scope atomics: a word is valid exactly when its generation matches, so no
 //     fence is needed and a stale value can never be mistaken for the current one.  Both are double
@@ -46,12 +50,14 @@ constexpr uint32_t kGenMask = 0x7FFFFFu;        // generation bits carried in a 
 constexpr int kMaxPairs = 1024;                 // (application, variant) pairs the reducer can hold
 constexpr int kSlotsPerThread = kMaxPairs / kRoundThreads;
 constexpr int kMaxAppGroups = 64;               // groups of one application a resident pair can serve
+constexpr int kAllToAllPairs = 128;             // up to this many pairs, every pair polls every slot itself
 static_assert(kWinCap <= kRoundThreads, "one window entry per thread");
 
 struct Persist {
   const int32_t* pair_app;      // [n_pairs] application of each pair
   const int32_t* pair_model;    // [n_pairs] variant of each pair
   int32_t n_pairs;
+  int32_t all_to_all;           // 1: every pair reads all pairs' slots and takes the maximum itself (no reducing workgroup)
   int32_t n_rounds;             // rounds this launch may run (<= kPersistRounds)
   int32_t spin_limit;           // polls before a wait between workgroups is given up (kSpinLimit unless a test shortens it)
   uint32_t gen_base;            // generations used by earlier launches
@@ -151,6 +157,7 @@ __device__ void persist_reduce_loop(const Tables& tb, const Window& w, const Per
                                     float* lat_win, float* swap_win, int* timed_out) {
   const int tid = threadIdx.x;
   const int B = tb.B;
+  if (ps.all_to_all) return;                      // every pair takes the maximum itself
   const int my_slot = tid < ps.n_pairs ? tid : 0;
   const int my_m = ps.pair_model[my_slot];
   if (tid == 0) {
@@ -341,7 +348,11 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
   int nb = 0, shift = 0;
   unsigned long long evals = 0ull;               // utility evaluations counted by this thread (lane 0 of a wavefront)
   for (int j = tid; j < B; j += kRoundThreads) lat_s[j] = tb.lat[((int64_t)a * tb.Mmax + m) * B + j];
-  if (tid == 0) timed_out = 0;
+  if (tid == 0) {
+    timed_out = 0;
+    if (ps.all_to_all && pair == 0) ps.ticks[0] = wall_clock64();
+  }
+  const int slot_model = ps.all_to_all && tid < ps.n_pairs ? ps.pair_model[tid] : 0;   // variant behind the slot this thread polls
   float4* went = reinterpret_cast<float4*>(sec_lds) + (size_t)wave * B;
   int32_t* wpos = reinterpret_cast<int32_t*>(sec_lds + (size_t)(kRoundThreads / 64) * B * sizeof(float4)) + (size_t)wave * B;
   __syncthreads();
@@ -519,8 +530,58 @@ __global__ __launch_bounds__(kRoundThreads, 6) void k_rounds_persistent(Tables t
     // (three dependent trips to memory, about twice the exchange: only once less than two windows are left)
     if (nb < min(2 * Bw, cap) && scan_end < seg_e) walk(1, 4);
 
-    // ---- wait for the decision ----
-    if (tid == 0) {
+    // ---- few pairs: the maximum over all pairs' slots, taken here (the reducer's rule on the same words) ----
+    if (ps.all_to_all) {
+      unsigned long long mine = 0ull, top = 0ull;
+      float mine_lat = 0.f, mine_swap = 0.f;
+      if (tid < ps.n_pairs) {
+        const unsigned long long* slot = ps.slots + ((size_t)(gen & 1u) * ps.n_pairs + tid) * 4;
+        unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull, v3 = 0ull;
+        bool ok = false;
+        for (int k = 0; k < ps.spin_limit; ++k) {
+          v0 = ld_dev(slot);
+          v1 = ld_dev(slot + 1);
+          v2 = ld_dev(slot + 2);
+          v3 = ld_dev(slot + 3);
+          ok = ((uint32_t)(v0 >> 9) & kGenMask) == (gen & kGenMask) && (uint32_t)(v1 & 0xFFFFull) == (gen & 0xFFFFu) &&
+               (uint32_t)(v2 & 0xFFFFFFFFull) == gen && (uint32_t)(v3 & 0xFFFFFFFFull) == gen;
+          if (ok) break;
+          __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok) {
+          timed_out = 1;
+        } else if (v0 & 0x100ull) {
+          const int pg = (int)((uint32_t)(v1 >> 16) & 0xFFFFu);
+          const uint32_t c2 = (uint32_t)((pg * tb.Mmax + slot_model) * B) + (uint32_t)(v0 & 0xffull);
+          mine = pack_candidate(__uint_as_float((uint32_t)(v0 >> 32)), c2);
+          mine_lat = __uint_as_float((uint32_t)(v1 >> 32));
+          mine_swap = __uint_as_float((uint32_t)(v2 >> 32));
+          top = ((unsigned long long)ordered_bits(__uint_as_float((uint32_t)(v3 >> 32))) << 32) |
+                (unsigned long long)(0xFFFFFFFFu - (uint32_t)pg);
+        }
+      }
+      if (tb.pol_group_first) {
+        top = block_max_u64(top, red);
+        if (top != 0ull && mine != 0ull) {
+          const int g_star = (int)(0xFFFFFFFFu - (uint32_t)(top & 0xFFFFFFFFull));
+          const uint32_t c2 = 0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull);
+          if ((int)(c2 / (uint32_t)B) / tb.Mmax != g_star) mine = 0ull;
+        }
+      }
+      const unsigned long long all = block_max_u64(mine, red);
+      if (all != 0ull && mine == all) {                          // candidate ids are unique: one writer
+        lat_win = mine_lat;
+        swap_win = mine_swap;
+      }
+      if (tid == 0) {
+        cid_win = all != 0ull ? (0xFFFFFFFFu - (uint32_t)(all & 0xFFFFFFFFull)) + 1u : 0u;
+        if (pair == 0) {                                         // for the commit workgroup, and the round's timestamp
+          st_dev(ps.dec + rl, all | (1ull << 63));
+          ps.ticks[rl + 1] = wall_clock64();
+        }
+      }
+    } else if (tid == 0) {
+      // ---- wait for the decision ----
       const unsigned long long* d = ps.decision + (size_t)(gen & 1u) * 4;
       unsigned long long v0 = 0ull, v1 = 0ull, v2 = 0ull;
       bool ok = false;

@@ -33,7 +33,7 @@ def request_at_a_time(w, ea, key, edf, max_accuracy):
     """Sec. 6.1: an ordering policy (EDF or the priority of eq. 12) and a per-request model choice:
     locally optimal (eq. 13: the variant with the best utility at the current time) or max accuracy (the
     most accurate variant that still meets the deadline).  Requests whose penalty is already 1 on the
-    fastest variant are skipped, as everywhere in this build."""
+    fastest variant are skipped, as everywhere in this library."""
     p, rq = w.profile, w.requests
     n = rq.app.shape[0]
     D = rq.deadline_rel_ms.astype(np.float64)
