@@ -298,16 +298,22 @@ def main():
         gbs_ = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None
         return {"name": name, "algorithmic_bytes": nbytes, "ms": ms, "gbs": gbs_,
                 "frac_of_hbm_peak": gbs_ / PEAK_HBM_GBS if gbs_ else None, "what": note}
+    # applications that fit one workgroup's LDS are ordered by one kernel that reads and writes each (key,
+    # position) pair once; longer ones take four radix passes over tiles (Sec. 5.2, eq. 12 ordering)
+    in_lds = (not args.split_groups) and A <= 1024 and int(np.max(counts)) <= 16384
+    order_b = 16 if in_lds else 68
+    order_note = ("one kernel per application: (key, position) read (8 B) and written (8 B) once, four passes in LDS" if in_lds
+                  else "digit totals of the keys (4 B) + four radix passes (8 B read, 8 B written each)")
     out["kernels"] = [
-        stream("group_by_app", 16 * N, g_ms, "digit totals of the application ids (4 B read per request) + one radix pass (4 B read, 8 B written)"),
-        stream("order_by_key_passes", 68 * N, o_ms - f_ms, "digit totals of the keys (4 B) + four radix passes (8 B read, 8 B written each)"),
+        stream("group_by_app", 32 * N, g_ms, "digit totals of the application ids (4 B read per request) + one radix pass (id 4 B, deadline and weight 8 B read; id, position 8 B and deadline, weight 8 B written)"),
+        stream("order_by_key_passes", order_b * N, o_ms - f_ms, order_note),
         stream("finish_order", 57 * N, f_ms, "position, 16-byte record and key read; id, deadline, weight, key, pending flag written; outputs reset"),
         stream("copy_outputs", 32 * N, c_ms, "four per-request outputs read and written"),
     ]
     out["hbm_copy_measured_gbs"] = binding.sp_debug_copy_rate(1 << 28)
     # the whole step against the scoring kernel's ceilings: its algorithmic flops and the algorithmic bytes of
     # every stage over the step's wall time (the rounds work on LDS-resident windows: no bytes counted for them)
-    step_bytes = k_bytes + (16 + 68 + 57 + 32) * N
+    step_bytes = k_bytes + (32 + order_b + 57 + 32) * N
     out["whole_step_roofline"] = {"algorithmic_flops": flops, "algorithmic_bytes": step_bytes,
                                   "tflops": flops / (ms_per_step * 1e-3) / 1e12,
                                   "frac_of_scoring_kernel_ceiling": flops / (ms_per_step * 1e-3) / 1e12 / peak_c,
