@@ -22,7 +22,7 @@ constexpr int kMlpH = 256;                       // padded hidden width (zero we
 constexpr int kL1Chunk = 64;                     // input channels per W1 slice
 constexpr int kL1Units = (kMlpH / 32) * (kL1Chunk / 16) * 64;   // 16-byte units per slice (2048 = 32 KB)
 constexpr int kL1PerThread = kL1Units / kMfThreads;             // 4
-constexpr int kL1Pre = 4;                                       // weight fragments in flight from LDS per wavefront
+constexpr int kL1Pre = 2;                                       // weight fragments in flight from LDS per wavefront
 
 // Bytes of one application's packed layer 1: its slices, then the bias padded with zeros to kMlpH floats.
 inline size_t mlp_layer1_bytes(int d) { return (size_t)((d + kL1Chunk - 1) / kL1Chunk) * kL1Units * 16 + kMlpH * sizeof(float); }
@@ -83,48 +83,51 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
 #pragma unroll
     for (int v = 0; v < 16; ++v) hacc[hb][v] = 0.f;
 
-  // slice 0 and the first feature pieces, the plain way
-  f32x4 xs[kL1Chunk / 16];
+  // Features travel two slices ahead of the matrix cores in a ring of three register sets (a slice's rows
+  // come from HBM: one slice of lead leaves the loop waiting for them), the W1 slice one ahead (L2).  All of
+  // these are ordinary loads, so the compiler counts what is in flight; a set is written in one step and read
+  // two steps later under its own name (the loop is unrolled by three), so nothing in flight is ever copied.
+  f32x4 x0[kL1Chunk / 16], x1[kL1Chunk / 16], x2[kL1Chunk / 16];
+  // d is a multiple of 8, so a lane's 16-byte piece lies wholly inside or outside a row; pieces outside are
+  // read from the row's start and zeroed by the slice that uses them (only a last, partial slice has any)
+  auto load_x = [&](f32x4 (&xs)[kL1Chunk / 16], int kc) {
+#pragma unroll
+    for (int s = 0; s < kL1Chunk / 16; ++s) {
+      const int k0 = kL1Chunk * kc + 16 * s;
+      xs[s] = *reinterpret_cast<const f32x4*>(row + (kc < nkc && k0 + 8 * g < d ? k0 : 0));
+    }
+  };
   {
     f32x4* dst = reinterpret_cast<f32x4*>(buf_b);
 #pragma unroll
     for (int i = 0; i < kL1PerThread; ++i) dst[tid + i * kMfThreads] = w1[tid + i * kMfThreads];
-#pragma unroll
-    for (int s = 0; s < kL1Chunk / 16; ++s) {
-      xs[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (16 * s + 8 * g < d) xs[s] = *reinterpret_cast<const f32x4*>(row + 16 * s);
-    }
+    load_x(x0, 0);
+    load_x(x1, 1);
   }
   __syncthreads();
-  f32x4 wst[kL1PerThread], xn[kL1Chunk / 16];
-#pragma unroll
-  for (int i = 0; i < kL1PerThread; ++i) wst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int s = 0; s < kL1Chunk / 16; ++s) xn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int kc = 0; kc < nkc; ++kc) {
+  // one slice: W1 slice kc + 1 and the features of slice kc + 2 start, the 32 MFMAs of slice kc run on xs
+  auto slice = [&](int kc, f32x4 (&xs)[kL1Chunk / 16], f32x4 (&xfar)[kL1Chunk / 16]) {
     const f32x4* cur = reinterpret_cast<const f32x4*>((kc & 1) ? buf_c : buf_b);
     f32x4* nxt = reinterpret_cast<f32x4*>((kc & 1) ? buf_b : buf_c);
-    const bool more = kc + 1 < nkc;
-    // next slice and next feature pieces: asynchronous loads pinned here (inline assembly, see stage_fetch);
-    // the last iteration re-reads its own slice into the idle buffer
+    // every step issues the same loads whatever is left to do (the last one reads its own slice again, into
+    // the idle buffer, and rows' starts for features that do not exist), so that the number of loads in
+    // flight behind any register is the same on every path and the waits the compiler inserts are exact
+    f32x4 wst[kL1PerThread];
     {
-      const f32x4* nsrc = w1 + (size_t)(more ? kc + 1 : kc) * kL1Units;
+      const f32x4* nsrc = w1 + (size_t)(kc + 1 < nkc ? kc + 1 : nkc - 1) * kL1Units;
 #pragma unroll
-      for (int i = 0; i < kL1PerThread; ++i) {
-        const f32x4* p = nsrc + tid + i * kMfThreads;
-        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wst[i]) : "v"(p) : "memory");
-      }
-      const int kb = kL1Chunk * (more ? kc + 1 : kc);
-#pragma unroll
-      for (int s = 0; s < kL1Chunk / 16; ++s) {
-        const int k0 = kb + 16 * s + 8 * g;
-        const uint16_t* p = row + (k0 < d ? kb + 16 * s : 0);          // out of range: any valid address, zeroed below
-        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(xn[s]) : "v"(p) : "memory");
-      }
+      for (int i = 0; i < kL1PerThread; ++i) wst[i] = nsrc[tid + i * kMfThreads];
     }
+    load_x(xfar, kc + 2);
+    __builtin_amdgcn_sched_barrier(0);
     // the slice's 32 weight fragments in the order they are used, each read kL1Pre fragments ahead of the
     // MFMA that takes it, so that LDS latency and matrix cores overlap inside a wavefront too
-    {
+    if (kc < nkc) {
+      if (kL1Chunk * (kc + 1) > d) {
+#pragma unroll
+        for (int s = 0; s < kL1Chunk / 16; ++s)
+          if (kL1Chunk * kc + 16 * s + 8 * g >= d) xs[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
       constexpr int kSteps = (kMlpH / 32) * (kL1Chunk / 16);
       f32x4 af[kL1Pre];
 #pragma unroll
@@ -138,21 +141,16 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(wst[0]), "+v"(wst[1]), "+v"(wst[2]), "+v"(wst[3]), "+v"(xn[0]), "+v"(xn[1]), "+v"(xn[2]), "+v"(xn[3])
-                 :
-                 : "memory");
 #pragma unroll
     for (int i = 0; i < kL1PerThread; ++i) nxt[tid + i * kMfThreads] = wst[i];
-    {
-      const int kb = kL1Chunk * (kc + 1);
-#pragma unroll
-      for (int s = 0; s < kL1Chunk / 16; ++s) {
-        const bool in = more && (kb + 16 * s + 8 * g < d);
-        xs[s] = in ? xn[s] : f32x4{0.f, 0.f, 0.f, 0.f};
-      }
-    }
     __syncthreads();
+  };
+  // whole trips of three steps (a step past the last slice only moves data nobody reads): the loop has one
+  // way in and one way round, so the counts of loads in flight are the same wherever a step is entered from
+  for (int kc = 0; kc < nkc; kc += 3) {
+    slice(kc, x0, x2);
+    slice(kc + 1, x1, x0);
+    slice(kc + 2, x2, x1);
   }
 
   // ---- bias, ReLU, per-request scale, split into half-precision hi + lo ----

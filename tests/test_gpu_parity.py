@@ -703,10 +703,11 @@ def test_logistic_widths_of_the_matrix_core_kernel(gpu, d):
     full_parity(gpu, w, max_rounds=20, want_cube=True)
 
 
-@pytest.mark.parametrize("d,H", [(8, 3), (72, 33), (136, 128), (264, 200), (512, 256), (40, 255)])
+@pytest.mark.parametrize("d,H", [(8, 3), (72, 33), (136, 128), (192, 64), (264, 200), (448, 96), (512, 256), (40, 255)])
 def test_bf16_mlp_widths_of_the_matrix_core_kernel(gpu, d, H):
-    """Input widths across the 64-channel slices of layer 1 (a ragged last slice included) and hidden widths
-    up to the kernel's 256."""
+    """Input widths across the 64-channel slices of layer 1 (a ragged last slice included; slice counts of
+    every remainder modulo three, the depth of the kernel's feature ring) and hidden widths up to the
+    kernel's 256."""
     w = wl.tiny(seed=7600 + d, n=900, classes=(70, 33, 5), models=(3, 16, 1), max_batch=9, feat_dim=d, hidden_dim=H,
                 feat_dtype=wl.BF16, deadline=(5.0, 80.0), fractions=(0.5, 0.3, 0.2))
     full_parity(gpu, w, max_rounds=20, ea_tol=2e-3)
