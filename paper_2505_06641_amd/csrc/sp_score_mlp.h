@@ -89,12 +89,13 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
   // two steps later under its own name (the loop is unrolled by three), so nothing in flight is ever copied.
   f32x4 x0[kL1Chunk / 16], x1[kL1Chunk / 16], x2[kL1Chunk / 16];
   // d is a multiple of 8, so a lane's 16-byte piece lies wholly inside or outside a row; pieces outside are
-  // read from the row's start and zeroed by the slice that uses them (only a last, partial slice has any)
+  // read from the start of the packed weights instead (one line that every workgroup has in cache anyway)
+  // and zeroed by the slice that uses them (only a last, partial slice has any)
   auto load_x = [&](f32x4 (&xs)[kL1Chunk / 16], int kc) {
 #pragma unroll
     for (int s = 0; s < kL1Chunk / 16; ++s) {
       const int k0 = kL1Chunk * kc + 16 * s;
-      xs[s] = *reinterpret_cast<const f32x4*>(row + (kc < nkc && k0 + 8 * g < d ? k0 : 0));
+      xs[s] = *((kc < nkc && k0 + 8 * g < d) ? reinterpret_cast<const f32x4*>(row + k0) : w1);
     }
   };
   {
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     const f32x4* cur = reinterpret_cast<const f32x4*>((kc & 1) ? buf_c : buf_b);
     f32x4* nxt = reinterpret_cast<f32x4*>((kc & 1) ? buf_b : buf_c);
     // every step issues the same loads whatever is left to do (the last one reads its own slice again, into
-    // the idle buffer, and rows' starts for features that do not exist), so that the number of loads in
+    // the idle buffer, and one cached line in place of features that do not exist), so that the number of loads in
     // flight behind any register is the same on every path and the waits the compiler inserts are exact
     f32x4 wst[kL1PerThread];
     {
