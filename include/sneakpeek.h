@@ -221,7 +221,12 @@ sp_status sp_debug_dump(sp_ctx* ctx, int32_t kind, void* stream, const void* x_d
  * HIP events around their stages; sp_set_timing(ctx, 2) additionally times
  * every round: from the rounds kernel's own constant-rate timestamps when the
  * rounds run in one launch, else from one HIP event after each of the first
- * 4096 rounds (this slows the rounds down a little).  sp_get_timing /
+ * 4096 rounds (this slows the rounds down a little); sp_set_timing(ctx, 3)
+ * records the two events around the scoring kernel only (an event between two
+ * kernels keeps the second from starting right behind the first: nine of them
+ * cost a window about 40 us, two about 10), and sp_get_timing then fills
+ * score_kernel_ms and leaves the other fields 0; 0 turns timing off.
+ * sp_get_timing /
  * sp_get_round_times wait for the events and return the elapsed device times
  * (per-round times in milliseconds, HOST array of `capacity` floats, *n_out =
  * number written).  SP_ESTATE if timing is off or nothing has been recorded yet. */

@@ -303,7 +303,7 @@ class Context:
                            "sp_set_swap_cost")
 
     def sp_set_timing(self, level=1):
-        """0 off, 1 stage events, 2 stage events and one event per round."""
+        """0 off, 1 stage events, 2 stage events and one event per round, 3 events around the scoring kernel only."""
         return self._check(self.lib.sp_set_timing(self.h, int(level)), "sp_set_timing")
 
     def sp_get_timing(self):

@@ -83,6 +83,7 @@ struct sp_ctx {
   std::string hip_err;
   // optional stage timing (benchmarks)
   bool timing = false;
+  bool timing_stages = false;            // an event after every stage (else only around the scoring kernel)
   bool timing_rounds = false;
   bool timed_score = false, timed_rounds = false;
   hipEvent_t ev[9] = {};                 // group start, score start, score stop, order stop, rounds start, rounds stop,
@@ -768,7 +769,8 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
   const bool tm = c->timing && n > 0;
   c->timed_score = false;
   c->timed_rounds = false;
-  if (tm) SP_HIP(c, hipEventRecord(c->ev[0], s));
+  const bool tms = tm && c->timing_stages;
+  if (tms) SP_HIP(c, hipEventRecord(c->ev[0], s));
 
   uint32_t *curK = c->bufK[0], *altK = c->bufK[1];
   int32_t *curV = c->bufV[0], *altV = c->bufV[1];
@@ -852,7 +854,7 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
         std::swap(v_out, v_spare);
       }
     }
-    if (tm) SP_HIP(c, hipEventRecord(c->ev[6], s));
+    if (tms) SP_HIP(c, hipEventRecord(c->ev[6], s));
     hipLaunchKernelGGL(k_finish_order, dim3((n + 255) / 256), dim3(256), 0, s, n, A, (const int32_t*)w.seg, v_in,
                        (const uint32_t*)k_in, w, c->tb.pol_edf | c->tb.pol_split);
     if (c->tb.pol_split) {
@@ -862,10 +864,8 @@ sp_status sp_score(sp_ctx* c, int32_t n, const void* x_dev, const int32_t* app_d
       hipLaunchKernelGGL(k_groups_compact, dim3(1), dim3(1024), 0, s, c->n_slots, (const int32_t*)c->slot_app,
                          (const int32_t*)c->slot_beg, (const int32_t*)c->slot_end, w);
     }
-    if (tm) {
-      SP_HIP(c, hipEventRecord(c->ev[3], s));
-      c->timed_score = true;
-    }
+    if (tms) SP_HIP(c, hipEventRecord(c->ev[3], s));
+    if (tm) c->timed_score = true;
     if (ea_out_dev)
       SP_HIP(c, hipMemcpyAsync(ea_out_dev, w.ea, (size_t)n * c->Mmax * sizeof(float), hipMemcpyDeviceToDevice, s));
     if (key_out_dev)
@@ -939,7 +939,7 @@ sp_status sp_schedule(sp_ctx* c, int32_t max_rounds, void* stream, int32_t* mode
   const int32_t start = c->rounds_done;
   sp_status st = SP_OK;
   bool fetched = false, outputs_copied = false;
-  const bool tm = c->timing;
+  const bool tm = c->timing && c->timing_stages;
   c->n_round_ev = 0;
   c->timed_rounds = false;
   c->timed_copy = false;
@@ -1059,7 +1059,8 @@ sp_status sp_set_timing(sp_ctx* c, int32_t enable) {
     for (hipEvent_t& e : c->round_ev) SP_HIP(c, hipEventCreate(&e));
   }
   c->timing = enable != 0;
-  c->timing_rounds = enable >= 2;
+  c->timing_stages = enable == 1 || enable == 2;
+  c->timing_rounds = enable == 2;
   c->timed_score = c->timed_rounds = false;
   return SP_OK;
 }
@@ -1071,11 +1072,14 @@ sp_status sp_get_timing(sp_ctx* c, sp_timing* out) {
   if (!g.ok) return SP_EDEVICE;
   sp_timing t{};
   if (c->timed_score) {
-    SP_HIP(c, hipEventSynchronize(c->ev[3]));
-    SP_HIP(c, hipEventElapsedTime(&t.group_ms, c->ev[0], c->ev[1]));
+    SP_HIP(c, hipEventSynchronize(c->ev[2]));
     SP_HIP(c, hipEventElapsedTime(&t.score_kernel_ms, c->ev[1], c->ev[2]));
-    SP_HIP(c, hipEventElapsedTime(&t.order_ms, c->ev[2], c->ev[3]));
-    SP_HIP(c, hipEventElapsedTime(&t.finish_order_ms, c->ev[6], c->ev[3]));
+    if (c->timing_stages) {
+      SP_HIP(c, hipEventSynchronize(c->ev[3]));
+      SP_HIP(c, hipEventElapsedTime(&t.group_ms, c->ev[0], c->ev[1]));
+      SP_HIP(c, hipEventElapsedTime(&t.order_ms, c->ev[2], c->ev[3]));
+      SP_HIP(c, hipEventElapsedTime(&t.finish_order_ms, c->ev[6], c->ev[3]));
+    }
   }
   if (c->timed_rounds) {
     SP_HIP(c, hipEventSynchronize(c->ev[5]));

@@ -766,6 +766,13 @@ def test_copy_rate_diagnostic_and_stage_timing(gpu):
         # loose deadlines: every round sees full windows of 7 requests in both applications
         rounds = summ["n_rounds"]
         assert tm["utility_evaluations"] == rounds * (2 + 3) * 7 * 8 // 2
+    # level 3: the two events around the scoring kernel only; the other fields stay 0
+    ctx.sp_set_timing(3)
+    ctx.sp_score(x, app, D, wt)
+    ctx.sp_schedule(3, model_out=model)
+    tm = ctx.sp_get_timing()
+    assert tm["score_kernel_ms"] > 0.0
+    assert tm["group_ms"] == 0.0 and tm["order_ms"] == 0.0 and tm["rounds_ms"] == 0.0 and tm["copy_outputs_ms"] == 0.0
     ctx.close()
 
 
