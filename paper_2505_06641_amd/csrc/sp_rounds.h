@@ -22,7 +22,11 @@ namespace sp {
 
 constexpr int kRoundThreads = 512;
 constexpr int kSmallGroup = 256;                  // remaining range up to which one wavefront scores a subgroup
-constexpr int kPairLanes = 8;                       // lanes that share one pair of batch sizes in the triangle
+// Lanes that share one pair of batch sizes in the triangle: 8 when the largest batch gives every group of 8
+// lanes of a 512-thread workgroup a pair (more than 64 requests), else 16, so that half the workgroup does not
+// sit idle.  A function of the largest batch alone: every kernel sums a score over the same lanes in the same
+// order, whatever the number of threads it brings.
+__device__ __forceinline__ int pair_lanes(int B) { return B > 64 ? 8 : 16; }
 
 // nthr: the threads of the workgroup that are still running (a power of two; the others have left).
 __device__ __forceinline__ double block_sum_f64(double v, double* scratch, int nthr = kRoundThreads) {
@@ -63,14 +67,15 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 
 // Score[a,m,b] for every batch size b over a candidate window of nb entries, and the best of them as a
 // packed candidate.  ent[j] = (key_j * EA[j,m], D_j, 1/D_j, 2 D_j); lat[b-1] = L[a][m][b].
-// Groups of kPairLanes lanes own the batch sizes (p+1, B-p), so all groups do the same amount of work;
+// Groups of kPairLanes = pair_lanes(B) lanes own the batch sizes (p+1, B-p), so all groups do the same amount of work;
 // both batch sizes of a pair run in the same loop (two independent chains per lane), and the completion
 // time of each batch size is carried as a float pair so that the loop stays in float32.
 // Every kernel that scores rounds calls this function: their scores agree bit for bit.
-template <int KIND>
+template <int KIND, int kPairLanes>
 __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* ent, const float* lat, int nb, int B,
                                                                 double t, uint32_t cid0, float* cube_out, int only_b,
                                                                 int nthr, int tid) {
+  static_assert(kPairLanes == 8 || kPairLanes == 16, "the sums below add over groups of 8 or 16 lanes");
   const int sub = tid % kPairLanes, grp = tid / kPairLanes;
   const int n_pairs = (B + 1) / 2;
   unsigned long long best = 0ull;
@@ -103,9 +108,8 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
       s2 += e.x * one_minus_penalty_f32<KIND>(e.y, e.w, e.z, e2h, e2l);
     }
     s2 += s3;
-    static_assert(kPairLanes == 8, "sum8 adds over groups of 8 lanes");
-    s1 = sum8(s1);
-    s2 = sum8(s2);
+    s1 = kPairLanes == 8 ? sum8(s1) : sum16(s1);
+    s2 = kPairLanes == 8 ? sum8(s2) : sum16(s2);
     if (sub == 0) {
       if (n1 > 0) {
         const unsigned long long pk = pack_candidate(s1, cid0 + (uint32_t)(b1 - 1));
@@ -124,14 +128,19 @@ __device__ __forceinline__ unsigned long long triangle_best_kind(const float4* e
 
 // nthr: the threads taking part (a multiple of 64), numbered tid = 0 .. nthr - 1 (by default the first nthr
 // threads of the workgroup; a single wavefront passes its lane number).  A score is summed by the same
-// kPairLanes lanes in the same order however many take part, so the result does not depend on it.
+// pair_lanes(B) lanes in the same order however many take part, so the result does not depend on it.
 __device__ __forceinline__ unsigned long long triangle_best(int kind, const float4* ent, const float* lat, int nb, int B,
                                                            double t, uint32_t cid0, float* cube_out, int only_b,
                                                            int nthr = kRoundThreads, int tid = -1) {
   if (tid < 0) tid = threadIdx.x;
-  if (kind == 0) return triangle_best_kind<0>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
-  if (kind == 1) return triangle_best_kind<1>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
-  return triangle_best_kind<2>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  if (pair_lanes(B) == 8) {
+    if (kind == 0) return triangle_best_kind<0, 8>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+    if (kind == 1) return triangle_best_kind<1, 8>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+    return triangle_best_kind<2, 8>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  }
+  if (kind == 0) return triangle_best_kind<0, 16>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  if (kind == 1) return triangle_best_kind<1, 16>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
+  return triangle_best_kind<2, 16>(ent, lat, nb, B, t, cid0, cube_out, only_b, nthr, tid);
 }
 
 // Utility evaluations (terms key * EA * (1 - penalty)) behind the candidates of one (group, variant) pair

@@ -64,4 +64,12 @@ __device__ __forceinline__ float sum8(float v) {
   return v;
 }
 
+// The same over each row of 16 lanes: after sum8 both halves of the row are uniform, so the mirrored lane
+// holds the other half's sum.
+__device__ __forceinline__ float sum16(float v) {
+  v = sum8(v);
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));   // row_mirror
+  return v;
+}
+
 }  // namespace sp
