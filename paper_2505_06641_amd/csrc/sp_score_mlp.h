@@ -44,6 +44,8 @@ inline void pack_mlp_layer1(const uint16_t* W1 /*[d,H] bf16 bits*/, int d, int H
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const f32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
+// DUMP: the launch only writes the logits (logits_out) and ends before the epilogue; dw_g and sortkey are
+// then null and must not be touched.
 template <bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_mlp_bf16(
     Tables tb, Window w, const uint16_t* __restrict__ x, const int32_t* __restrict__ ids, const float2* __restrict__ dw_g,

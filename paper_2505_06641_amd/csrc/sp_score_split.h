@@ -636,6 +636,8 @@ __device__ __forceinline__ int xcd_tile(int wg, int n_tiles) {
   return (j < per && tile < n_tiles) ? tile : -1;
 }
 
+// DUMP: the launch only writes the logits (logits_out) and ends before the epilogue; dw_g and sortkey are
+// then null and must not be touched.
 template <int D, bool DUMP, bool SPLIT>
 __global__ __launch_bounds__(kMfThreads) void k_score_logistic_split(
     Tables tb, Window w, const float* __restrict__ x, const int32_t* __restrict__ ids, const float2* __restrict__ dw_g,
